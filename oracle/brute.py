@@ -1,0 +1,128 @@
+"""Second, deliberately different implementation: exact rationals and loops.
+
+Test infrastructure only; used on tiny inputs to pin oracle.formats and
+oracle.arcquant.  Nothing is shared with them: the grids are rebuilt from
+the bit-field definitions (Appendix A, Table "formats": E2M1 bias 1,
+E4M3 bias 7), fp32 rounding is done by hand on fractions.Fraction values,
+nearest-value searches are argmin loops, and the GEMM is a triple loop
+over the sum in Section 3.2 eq. (2).
+"""
+from fractions import Fraction as Fr
+
+
+def e2m1_value(code):
+    s, e, m = (code >> 3) & 1, (code >> 1) & 3, code & 1
+    mag = Fr(m, 2) if e == 0 else (1 + Fr(m, 2)) * Fr(2) ** (e - 1)
+    return -mag if s else mag
+
+
+def e4m3_value(byte):
+    s, e, m = (byte >> 7) & 1, (byte >> 3) & 15, byte & 7
+    if e == 15 and m == 7:
+        raise ValueError("NaN pattern")
+    mag = Fr(m, 8) * Fr(2) ** -6 if e == 0 else (1 + Fr(m, 8)) * Fr(2) ** (e - 7)
+    return -mag if s else mag
+
+
+def _nearest_even(x, candidates):
+    """candidates: list of (code, value) with value >= 0; nearest to x, tie -> even code;
+    x beyond the largest value goes to the largest value."""
+    best = None
+    for code, val in candidates:
+        d = abs(x - val)
+        if best is None or d < best[0] or (d == best[0] and code % 2 == 0):
+            best = (d, code)
+    return best[1]
+
+
+_E2M1_POS = [(c, e2m1_value(c)) for c in range(8)]
+_E4M3_POS = [(b, e4m3_value(b)) for b in range(0x7F)]
+
+
+def e2m1_nearest(w):
+    return _nearest_even(Fr(w), _E2M1_POS)
+
+
+def e4m3_nearest_sat(u):
+    return _nearest_even(Fr(u), _E4M3_POS)
+
+
+def round_f32(q):
+    """Round a rational to the nearest IEEE binary32 value (ties to even), as a Fraction.
+    Subnormals are kept; overflow is not handled (never reached by the tests)."""
+    q = Fr(q)
+    if q == 0:
+        return q
+    a = abs(q)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fr(2) ** e > a:
+        e -= 1
+    assert Fr(2) ** e <= a < Fr(2) ** (e + 1)
+    e = max(e, -126)
+    quantum = Fr(2) ** (e - 23)
+    n = round(a / quantum)          # Python rounds Fractions half-to-even
+    r = n * quantum
+    return -r if q < 0 else r
+
+
+def quantize_block(v, s_T):
+    """v: 16 numbers exactly representable in fp32 (floats or Fractions), s_T fp32-valued.
+    Returns (scale_byte, [16 codes], [16 residuals as Fractions]).
+    Same recipe as oracle.arcquant's header, every fp32 rounding done by round_f32."""
+    v = [Fr(x) for x in v]
+    neg = [(x < 0) for x in v]
+    s_T = Fr(s_T)
+    ginv = round_f32(1 / round_f32(6 * s_T))
+    amax = max(abs(x) for x in v)
+    u = round_f32(amax * ginv)
+    sb = e4m3_nearest_sat(u)
+    s = round_f32(e4m3_value(sb) * s_T)
+    codes, res = [], []
+    for x, n in zip(v, neg):
+        if s == 0:
+            idx = 0
+        else:
+            inv = round_f32(1 / s)
+            w = round_f32(abs(x) * inv)
+            idx = e2m1_nearest(min(w, Fr(6)))
+        code = (8 if n else 0) | idx
+        codes.append(code)
+        res.append(round_f32(x - e2m1_value(code) * s))
+    return sb, codes, res
+
+
+def quantize_block_real(v, s_T):
+    """The same block under exact real arithmetic for the element division
+    (codes = nearest-even of |v| / s with the true quotient).  Diagnostic only:
+    shows how often the fp32 reciprocal-multiply recipe departs from eq. (1)
+    evaluated in real numbers."""
+    v = [Fr(x) for x in v]
+    s_T = Fr(s_T)
+    ginv = round_f32(1 / round_f32(6 * s_T))
+    u = round_f32(max(abs(x) for x in v) * ginv)
+    sb = e4m3_nearest_sat(u)
+    s = round_f32(e4m3_value(sb) * s_T)
+    codes = []
+    for x in v:
+        idx = 0 if s == 0 else e2m1_nearest(min(abs(x) / s, Fr(6)))
+        codes.append((8 if x < 0 else 0) | idx)
+    return sb, codes
+
+
+def gemm_loops(a_codes, a_scales, a_sT, w_codes, w_scales, w_sT):
+    """Y[m][n] = s_Ta s_Tw sum_b sx[m][b] sw[n][b] sum_i qx[m][16b+i] qw[n][16b+i]
+    (Section 3.2 eq. (2)); a_codes / w_codes are UNPACKED 4-bit codes per element
+    (lists of lists), scales are E4M3 bytes per block.  Exact, returns Fractions."""
+    M, N = len(a_codes), len(w_codes)
+    Kp = len(a_codes[0])
+    Y = [[Fr(0)] * N for _ in range(M)]
+    for m in range(M):
+        for n in range(N):
+            acc = Fr(0)
+            for b in range(Kp // 16):
+                dot = Fr(0)
+                for i in range(16):
+                    dot += e2m1_value(a_codes[m][16 * b + i]) * e2m1_value(w_codes[n][16 * b + i])
+                acc += e4m3_value(a_scales[m][b]) * e4m3_value(w_scales[n][b]) * dot
+            Y[m][n] = acc * Fr(a_sT) * Fr(w_sT)
+    return Y
