@@ -1,0 +1,131 @@
+/*
+ * arcq.h -- C ABI of libarcq: the ARCQuant hot path on AMD MI355X (gfx950).
+ *
+ * ARCQuant (arXiv 2601.07475) runs a W4A4 linear layer Y = X W^T in NVFP4 and
+ * repairs the quantization error of the S largest-magnitude activation
+ * channels by appending their quantized residual as S extra reduction columns,
+ * so that one GEMM over K' = K + S computes
+ *     Y ~= Q(X) Q(W)^T + Q(R_o) Q(W_o)^T                      (Section 3.2, eq. (2)).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or synchronises; work is enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and results
+ *     are valid in stream order.  Inputs are never modified.
+ *   - Return value: ARCQ_OK or an error code; arcq_last_error() then holds a
+ *     message.  Argument errors are detected before any HIP call is made.
+ *   - NVFP4 (Appendix A, Table "formats"): elements are FP4 E2M1 (bias 1,
+ *     magnitudes 0 .5 1 1.5 2 3 4 6), one FP8 E4M3 scale (bias 7, max 448,
+ *     finite flavour) per block of 16 consecutive reordered channels, one
+ *     FP32 scale per tensor.  Value = E2M1(code) * E4M3(scale byte) * tensor_scale.
+ *   - Packed operand layout ("K' layout"), rows = M for activations, N for weights:
+ *       codes  uint8 [rows, K'/2]   byte i of a row: element 2i in bits 0-3,
+ *                                   element 2i+1 in bits 4-7; code = sign<<3 | index
+ *       scales uint8 [rows, K'/16]  block b < K/16: primary block b;
+ *                                   block K/16 + i: augmented block of primary
+ *                                   block (K-S)/16 + i                 (Section 3.2 step (3))
+ *     Rows are dense (pitch K'/2 and K'/16 bytes).
+ *   - Shapes: K > 0, K % 16 == 0, 0 <= S <= K, S % 16 == 0, K <= ARCQ_MAX_K.
+ *     rows may be 0 (nothing is launched).
+ *   - Inputs must be finite; the result for NaN/Inf input is unspecified.
+ */
+#ifndef ARCQ_H
+#define ARCQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int arcq_status;
+#define ARCQ_OK                  0
+#define ARCQ_INVALID_ARG         1   /* null pointer, tensor scale not finite / not in (2^-64, 2^64), bad dtype */
+#define ARCQ_BAD_SHAPE           2   /* violates the shape rules above, or ld < row length */
+#define ARCQ_BAD_ALIGN           3   /* pointer / leading dimension alignment, see each function */
+#define ARCQ_HIP_ERROR           4   /* a launch failed; arcq_last_error() has the HIP message */
+#define ARCQ_WORKSPACE_TOO_SMALL 5
+
+#define ARCQ_MAX_K 65536             /* one fp16 row must fit the 160 KB LDS of a CU with room to spare */
+
+#define ARCQ_DTYPE_F16 0
+#define ARCQ_DTYPE_F32 1
+
+/* Library version, major*10000 + minor*100 + patch. */
+int arcq_version(void);
+
+/* Message of the last error on the calling thread ("" if none).  The string is
+ * thread-local storage of the library; do not free it. */
+const char* arcq_last_error(void);
+
+/* Bytes a caller must allocate for a packed operand of `rows` rows:
+ *   *codes_bytes = rows*(K+S)/2, *scales_bytes = rows*(K+S)/16.   Host arithmetic only. */
+arcq_status arcq_packed_sizes(int64_t rows, int64_t K, int64_t S,
+                              size_t* codes_bytes, size_t* scales_bytes);
+
+/*
+ * Online activation quantizer, one fused pass (Section 3.2 "Online Activation
+ * Quantization" steps (1)-(3); Section 3.3 fused kernel without the RMSNorm):
+ *   (1) reorder: Xp[m, j] = x[m, perm[j]]; per block of 16: scale byte =
+ *       E4M3(amax / (6 * tensor_scale)), codes = E2M1(Xp / s), s = E4M3 value * tensor_scale
+ *       (Section 3.1 eq. (1), round-to-nearest-even, saturating);
+ *   (2) on the last S reordered channels: r = Xp - s * Q, quantized the same way
+ *       with the same tensor_scale;
+ *   (3) output [Q_X | Q_R], [s_X | s_R] in the K' layout.
+ * x       fp16 [M, K], row pitch ldx elements (ldx >= K); x 16-byte aligned, ldx % 8 == 0
+ * perm    int32 [K], a permutation of 0..K-1 (not checked; see arcq_check_perm):
+ *         reordered position j takes source channel perm[j]; outliers are the LAST S positions
+ * codes   out, uint8 [M, (K+S)/2], 8-byte aligned;  scales out, uint8 [M, (K+S)/16]
+ */
+arcq_status arcq_quantize_act(const void* x, int64_t M, int64_t K, int64_t ldx,
+                              const int32_t* perm, int64_t S, float tensor_scale,
+                              uint8_t* codes, uint8_t* scales, void* stream);
+
+/*
+ * Offline weight packer (Section 3.2 "Offline Weight Quantization"): reorder the
+ * K axis of w with the same perm, quantize every block of 16 (plain
+ * round-to-nearest), then append a verbatim copy of the codes and scale bytes of
+ * the last S reordered channels: Q_Waug = [Q_W | Q_Wo].
+ * w  fp16 [N, K] (nn.Linear layout, Y = X W^T), row pitch ldw; same alignment rules as x.
+ */
+arcq_status arcq_pack_weight(const void* w, int64_t N, int64_t K, int64_t ldw,
+                             const int32_t* perm, int64_t S, float tensor_scale,
+                             uint8_t* codes, uint8_t* scales, void* stream);
+
+/* Bytes of workspace arcq_gemm needs for this problem (may be 0).  Host arithmetic only. */
+arcq_status arcq_gemm_workspace_size(int64_t M, int64_t N, int64_t Kp, size_t* bytes);
+
+/*
+ * The single GEMM over the extended reduction dimension (Section 3.2 "Unified
+ * GEMM Execution", eq. (2)):
+ *   y[m, n] = a_tensor_scale * w_tensor_scale *
+ *             sum_{b < Kp/16} sa[m,b] * sw[n,b] * sum_{i<16} qa[m,16b+i] * qw[n,16b+i]
+ * with fp32 accumulation.  Operands are decoded exactly (every code*scale
+ * product fits fp16) and multiplied on the fp16 MFMA path.
+ * a_*  packed activations [M, Kp] from arcq_quantize_act;  w_*  packed weights [N, Kp]
+ *      from arcq_pack_weight; codes 8-byte aligned.  Kp % 16 == 0, Kp > 0.
+ * y    out [M, N] row-major, pitch ldy elements (ldy >= N), y_dtype ARCQ_DTYPE_F16 / _F32,
+ *      4-byte aligned.
+ * workspace  device scratch of at least arcq_gemm_workspace_size bytes, 256-byte
+ *      aligned (may be NULL when that size is 0); contents undefined afterwards.
+ */
+arcq_status arcq_gemm(const uint8_t* a_codes, const uint8_t* a_scales, float a_tensor_scale,
+                      const uint8_t* w_codes, const uint8_t* w_scales, float w_tensor_scale,
+                      int64_t M, int64_t N, int64_t Kp,
+                      void* y, int y_dtype, int64_t ldy,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Debug helper: checks on the device that perm[0..K-1] is a permutation of 0..K-1
+ * (the calibration output of Section 3.2 "Adaptive Outlier Identification").
+ * flags: device scratch, K bytes.  *result_host is written after the stream has been
+ * synchronised by this call: 1 = valid, 0 = not a permutation.
+ */
+arcq_status arcq_check_perm(const int32_t* perm, int64_t K, uint8_t* flags,
+                            int* result_host, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARCQ_H */

@@ -1,0 +1,144 @@
+"""Thin ctypes binding of libarcq.so: same names as include/arcq.h, argument marshalling only.
+
+PyTorch supplies device memory and the stream; every step of the path runs in the HIP
+kernels.  There is no fallback: if the library is not built, or a call fails, an exception
+is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libarcq.so")
+
+OK, INVALID_ARG, BAD_SHAPE, BAD_ALIGN, HIP_ERROR, WORKSPACE_TOO_SMALL = range(6)
+DTYPE_F16, DTYPE_F32 = 0, 1
+MAX_K = 65536
+
+# every symbol include/arcq.h declares: name -> (restype, argtypes)
+_i64, _f32, _vp, _sz = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+SIGNATURES = {
+    "arcq_version": (ctypes.c_int, []),
+    "arcq_last_error": (ctypes.c_char_p, []),
+    "arcq_packed_sizes": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
+    "arcq_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _vp, _vp, _vp]),
+    "arcq_pack_weight": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _vp, _vp, _vp]),
+    "arcq_gemm_workspace_size": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
+    "arcq_gemm": (ctypes.c_int, [_vp, _vp, _f32, _vp, _vp, _f32, _i64, _i64, _i64, _vp, ctypes.c_int, _i64,
+                                 _vp, _sz, _vp]),
+    "arcq_check_perm": (ctypes.c_int, [_vp, _i64, _vp, ctypes.POINTER(ctypes.c_int), _vp]),
+}
+
+
+class ArcqError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"libarcq status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2601_07475_amd.build`")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def _check(status):
+    if status != OK:
+        raise ArcqError(status, lib().arcq_last_error().decode())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr() if t is not None and t.numel() else 0) if t is not None else None
+
+
+def arcq_version():
+    return lib().arcq_version()
+
+
+def arcq_packed_sizes(rows, K, S):
+    c, s = _sz(0), _sz(0)
+    _check(lib().arcq_packed_sizes(rows, K, S, ctypes.byref(c), ctypes.byref(s)))
+    return c.value, s.value
+
+
+def _quantize(fn, x, perm, S, tensor_scale, codes=None, scales=None):
+    assert x.is_cuda and x.dtype == torch.float16 and x.dim() == 2 and x.stride(1) == 1
+    assert perm.is_cuda and perm.dtype == torch.int32 and perm.is_contiguous()
+    rows, K = x.shape
+    if perm.numel() != K:
+        raise ArcqError(BAD_SHAPE, "perm must have K entries")
+    ldx = x.stride(0) if rows > 1 else max(K, x.stride(0))
+    cb, sb = arcq_packed_sizes(rows, K, S)
+    Kp = K + S
+    if codes is None:
+        codes = torch.empty((rows, Kp // 2), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows, Kp // 16), dtype=torch.uint8, device=x.device)
+    assert codes.numel() == cb and scales.numel() == sb and codes.is_contiguous() and scales.is_contiguous()
+    _check(fn(_ptr(x), rows, K, ldx, _ptr(perm), S, float(tensor_scale), _ptr(codes), _ptr(scales), _stream()))
+    return codes, scales
+
+
+def arcq_quantize_act(x, perm, S, tensor_scale, codes=None, scales=None):
+    """x fp16 [M, K] cuda, perm int32 [K] cuda -> (codes uint8 [M, K'/2], scales uint8 [M, K'/16])."""
+    return _quantize(lib().arcq_quantize_act, x, perm, S, tensor_scale, codes, scales)
+
+
+def arcq_pack_weight(w, perm, S, tensor_scale, codes=None, scales=None):
+    """w fp16 [N, K] cuda -> packed [N, K'] with the outlier blocks duplicated."""
+    return _quantize(lib().arcq_pack_weight, w, perm, S, tensor_scale, codes, scales)
+
+
+def arcq_gemm_workspace_size(M, N, Kp):
+    b = _sz(0)
+    _check(lib().arcq_gemm_workspace_size(M, N, Kp, ctypes.byref(b)))
+    return b.value
+
+
+def arcq_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale,
+              out_dtype=torch.float16, y=None, workspace=None):
+    """y[M, N] = deq(A) deq(W)^T over K' (fp32 accumulate); returns y."""
+    for t in (a_codes, a_scales, w_codes, w_scales):
+        assert t.is_cuda and t.dtype == torch.uint8 and t.is_contiguous()
+    M, N = a_codes.shape[0], w_codes.shape[0]
+    Kp = a_codes.shape[1] * 2
+    if w_codes.shape[1] * 2 != Kp or a_scales.shape != (M, Kp // 16) or w_scales.shape != (N, Kp // 16):
+        raise ArcqError(BAD_SHAPE, "operand shapes disagree on K'")
+    if y is None:
+        y = torch.empty((M, N), dtype=out_dtype, device=a_codes.device)
+    assert y.shape == (M, N) and y.stride(1) == 1 and y.dtype in (torch.float16, torch.float32)
+    need = arcq_gemm_workspace_size(M, N, Kp)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=a_codes.device)
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    ldy = y.stride(0) if M > 1 else max(N, y.stride(0))
+    _check(lib().arcq_gemm(_ptr(a_codes), _ptr(a_scales), float(a_tensor_scale),
+                           _ptr(w_codes), _ptr(w_scales), float(w_tensor_scale), M, N, Kp,
+                           _ptr(y), DTYPE_F16 if y.dtype == torch.float16 else DTYPE_F32, ldy,
+                           _ptr(workspace) if workspace is not None else None, ws_bytes, _stream()))
+    return y
+
+
+def arcq_check_perm(perm):
+    """True if the int32 cuda tensor perm is a permutation of 0..K-1 (synchronises)."""
+    K = perm.numel()
+    flags = torch.empty(K, dtype=torch.uint8, device=perm.device)
+    res = ctypes.c_int(-1)
+    _check(lib().arcq_check_perm(_ptr(perm), K, _ptr(flags), ctypes.byref(res), _stream()))
+    return res.value == 1

@@ -1,0 +1,145 @@
+// C entry points of libarcq: argument validation (before any HIP call), then launch.
+#include "internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+namespace arcq {
+
+namespace {
+thread_local char g_err[512] = "";
+}
+
+arcq_status fail(arcq_status code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+arcq_status check_launch(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "%s: %s", what, hipGetErrorString(e));
+    return ARCQ_OK;
+}
+
+namespace {
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+arcq_status check_scale(float s, const char* name) {
+    if (!std::isfinite(s) || !(s > 0x1p-64f) || !(s < 0x1p64f))
+        return fail(ARCQ_INVALID_ARG, "%s = %g: must be finite and within (2^-64, 2^64)", name, (double)s);
+    return ARCQ_OK;
+}
+
+arcq_status check_KS(int64_t K, int64_t S) {
+    if (K <= 0 || (K % 16) != 0) return fail(ARCQ_BAD_SHAPE, "K = %lld: must be > 0 and a multiple of 16", (long long)K);
+    if (K > ARCQ_MAX_K) return fail(ARCQ_BAD_SHAPE, "K = %lld exceeds ARCQ_MAX_K = %d", (long long)K, ARCQ_MAX_K);
+    if (S < 0 || S > K || (S % 16) != 0)
+        return fail(ARCQ_BAD_SHAPE, "S = %lld: must satisfy 0 <= S <= K and S %% 16 == 0", (long long)S);
+    return ARCQ_OK;
+}
+
+arcq_status quantize_entry(int mode, const char* who, const void* x, int64_t rows, int64_t K, int64_t ldx,
+                           const int32_t* perm, int64_t S, float s_T, uint8_t* codes, uint8_t* scales,
+                           void* stream) {
+    clear_error();
+    if (arcq_status st = check_KS(K, S)) return st;
+    if (rows < 0 || rows > 0x7FFFFFFF) return fail(ARCQ_BAD_SHAPE, "%s: rows = %lld out of range", who, (long long)rows);
+    if (ldx < K) return fail(ARCQ_BAD_SHAPE, "%s: leading dimension %lld < K = %lld", who, (long long)ldx, (long long)K);
+    if (arcq_status st = check_scale(s_T, "tensor_scale")) return st;
+    if (rows == 0) return ARCQ_OK;
+    if (!x || !perm || !codes || !scales) return fail(ARCQ_INVALID_ARG, "%s: null pointer", who);
+    if (!aligned(x, 16) || (ldx % 8) != 0)
+        return fail(ARCQ_BAD_ALIGN, "%s: input must be 16-byte aligned with a leading dimension that is a multiple of 8", who);
+    if (!aligned(codes, 8)) return fail(ARCQ_BAD_ALIGN, "%s: codes must be 8-byte aligned", who);
+    if (!aligned(perm, 4)) return fail(ARCQ_BAD_ALIGN, "%s: perm must be 4-byte aligned", who);
+    return launch_quantize(mode, x, rows, K, ldx, perm, S, s_T, codes, scales, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+}  // namespace arcq
+
+using namespace arcq;
+
+extern "C" {
+
+int arcq_version(void) { return 100; }
+
+const char* arcq_last_error(void) { return g_err; }
+
+arcq_status arcq_packed_sizes(int64_t rows, int64_t K, int64_t S, size_t* codes_bytes, size_t* scales_bytes) {
+    clear_error();
+    if (arcq_status st = check_KS(K, S)) return st;
+    if (rows < 0) return fail(ARCQ_BAD_SHAPE, "rows = %lld < 0", (long long)rows);
+    if (!codes_bytes || !scales_bytes) return fail(ARCQ_INVALID_ARG, "null output pointer");
+    *codes_bytes = (size_t)rows * (size_t)(K + S) / 2;
+    *scales_bytes = (size_t)rows * (size_t)(K + S) / 16;
+    return ARCQ_OK;
+}
+
+arcq_status arcq_quantize_act(const void* x, int64_t M, int64_t K, int64_t ldx, const int32_t* perm, int64_t S,
+                              float tensor_scale, uint8_t* codes, uint8_t* scales, void* stream) {
+    return quantize_entry(0, "arcq_quantize_act", x, M, K, ldx, perm, S, tensor_scale, codes, scales, stream);
+}
+
+arcq_status arcq_pack_weight(const void* w, int64_t N, int64_t K, int64_t ldw, const int32_t* perm, int64_t S,
+                             float tensor_scale, uint8_t* codes, uint8_t* scales, void* stream) {
+    return quantize_entry(1, "arcq_pack_weight", w, N, K, ldw, perm, S, tensor_scale, codes, scales, stream);
+}
+
+static arcq_status check_gemm_shape(int64_t M, int64_t N, int64_t Kp) {
+    if (M < 0 || N < 0 || M > 0x7FFFFFFF || N > 0x7FFFFFFF)
+        return fail(ARCQ_BAD_SHAPE, "M = %lld, N = %lld out of range", (long long)M, (long long)N);
+    if (Kp <= 0 || (Kp % 16) != 0 || Kp > 2 * (int64_t)ARCQ_MAX_K)
+        return fail(ARCQ_BAD_SHAPE, "K' = %lld: must be a positive multiple of 16, at most %d", (long long)Kp, 2 * ARCQ_MAX_K);
+    return ARCQ_OK;
+}
+
+arcq_status arcq_gemm_workspace_size(int64_t M, int64_t N, int64_t Kp, size_t* bytes) {
+    clear_error();
+    if (arcq_status st = check_gemm_shape(M, N, Kp)) return st;
+    if (!bytes) return fail(ARCQ_INVALID_ARG, "null output pointer");
+    *bytes = gemm_workspace_bytes(M, N, Kp);
+    return ARCQ_OK;
+}
+
+arcq_status arcq_gemm(const uint8_t* a_codes, const uint8_t* a_scales, float a_tensor_scale,
+                      const uint8_t* w_codes, const uint8_t* w_scales, float w_tensor_scale,
+                      int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    if (arcq_status st = check_gemm_shape(M, N, Kp)) return st;
+    if (y_dtype != ARCQ_DTYPE_F16 && y_dtype != ARCQ_DTYPE_F32) return fail(ARCQ_INVALID_ARG, "y_dtype = %d", y_dtype);
+    if (ldy < N) return fail(ARCQ_BAD_SHAPE, "ldy = %lld < N = %lld", (long long)ldy, (long long)N);
+    if (arcq_status st = check_scale(a_tensor_scale, "a_tensor_scale")) return st;
+    if (arcq_status st = check_scale(w_tensor_scale, "w_tensor_scale")) return st;
+    if (M == 0 || N == 0) return ARCQ_OK;
+    if (!a_codes || !a_scales || !w_codes || !w_scales || !y) return fail(ARCQ_INVALID_ARG, "arcq_gemm: null pointer");
+    if (!aligned(a_codes, 8) || !aligned(w_codes, 8)) return fail(ARCQ_BAD_ALIGN, "arcq_gemm: codes must be 8-byte aligned");
+    if (!aligned(y, 4)) return fail(ARCQ_BAD_ALIGN, "arcq_gemm: y must be 4-byte aligned");
+    const size_t need = gemm_workspace_bytes(M, N, Kp);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need)
+            return fail(ARCQ_WORKSPACE_TOO_SMALL, "arcq_gemm: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+        if (!aligned(workspace, 256)) return fail(ARCQ_BAD_ALIGN, "arcq_gemm: workspace must be 256-byte aligned");
+    }
+    // alpha in fp32: one rounding of the product of the two tensor scales
+    const float alpha = a_tensor_scale * w_tensor_scale;
+    return launch_gemm(a_codes, a_scales, w_codes, w_scales, M, N, Kp, alpha, y, y_dtype, ldy, workspace,
+                       workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+arcq_status arcq_check_perm(const int32_t* perm, int64_t K, uint8_t* flags, int* result_host, void* stream) {
+    clear_error();
+    if (K <= 0 || K > ARCQ_MAX_K) return fail(ARCQ_BAD_SHAPE, "K = %lld out of range", (long long)K);
+    if (!perm || !flags || !result_host) return fail(ARCQ_INVALID_ARG, "arcq_check_perm: null pointer");
+    return launch_check_perm(perm, K, flags, result_host, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,33 @@
+// Internal declarations shared by the translation units of libarcq (host side only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/arcq.h"
+
+namespace arcq {
+
+// Records a message for arcq_last_error() and returns `code`.
+arcq_status fail(arcq_status code, const char* fmt, ...);
+void clear_error();
+
+// After a kernel launch: turns a pending HIP launch error into ARCQ_HIP_ERROR.
+arcq_status check_launch(const char* what);
+
+// mode 0: activations (residual blocks appended); mode 1: weights (outlier blocks duplicated).
+arcq_status launch_quantize(int mode, const void* x, int64_t rows, int64_t K, int64_t ldx,
+                            const int32_t* perm, int64_t S, float s_T,
+                            uint8_t* codes, uint8_t* scales, hipStream_t stream);
+
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t Kp);
+arcq_status launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
+                        const uint8_t* w_codes, const uint8_t* w_scales,
+                        int64_t M, int64_t N, int64_t Kp, float alpha,
+                        void* y, int y_dtype, int64_t ldy,
+                        void* workspace, size_t workspace_bytes, hipStream_t stream);
+
+arcq_status launch_check_perm(const int32_t* perm, int64_t K, uint8_t* flags,
+                              int* result_host, hipStream_t stream);
+
+}  // namespace arcq

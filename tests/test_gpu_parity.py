@@ -1,0 +1,277 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element.
+
+Bars: codes and scale bytes bit-exact; GEMM within 1e-3 of the fp64 oracle in the normalised
+max error  max_ij |Y - Yref| / max(|Yref_ij|, rms(Yref))  (element-wise relative error is
+unbounded at cancellation zeros), fp32 accumulate.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import arcquant as A
+from paper_2601_07475_amd import binding as B
+from paper_2601_07475_amd import workloads as wk
+
+pytestmark = pytest.mark.gpu
+
+GEMM_TOL_F16 = 1e-3      # fp16 output: half an ulp of fp16 is 2^-11 = 4.9e-4
+GEMM_TOL_F32 = 2e-5      # fp32 output: only fp32 accumulation order differs from fp64
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def norm_err(Y, Yref):
+    Y = np.asarray(Y, dtype=np.float64)
+    rms = np.sqrt(np.mean(Yref ** 2))
+    return float(np.max(np.abs(Y - Yref) / np.maximum(np.abs(Yref), max(rms, 1e-300))))
+
+
+def guarded_empty(shape, fill=0xA5):
+    """uint8 buffer with 256 guard bytes on both sides, to catch out-of-bounds stores."""
+    n = int(np.prod(shape))
+    n_al = (n + 255) // 256 * 256
+    raw = torch.full((n_al + 512,), fill, dtype=torch.uint8, device="cuda")
+    return raw, raw[256:256 + n].view(*shape)
+
+
+def guards_intact(raw, n, fill=0xA5):
+    n_al = (n + 255) // 256 * 256
+    r = raw.cpu().numpy()
+    return bool(np.all(r[:256] == fill) and np.all(r[256 + n:] == fill)) and len(r) == n_al + 512
+
+
+def gpu_quantize(fn, X, perm, S, sT):
+    rows, K = X.shape
+    Kp = K + S
+    raw_c, codes = guarded_empty((rows, Kp // 2))
+    raw_s, scales = guarded_empty((rows, Kp // 16))
+    fn(dev(X), dev(perm.astype(np.int32)), S, sT, codes=codes, scales=scales)
+    torch.cuda.synchronize()
+    assert guards_intact(raw_c, rows * Kp // 2) and guards_intact(raw_s, rows * Kp // 16)
+    return codes.cpu().numpy(), scales.cpu().numpy()
+
+
+def assert_same_bytes(got, want, what):
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        raise AssertionError(f"{what}: {len(bad)} of {want.size} bytes differ; first at {bad[0].tolist()}: "
+                             f"got {got[tuple(bad[0])]:#x} want {want[tuple(bad[0])]:#x}")
+
+
+def rand_case(M, K, N, S, seed, kind="loguniform20_100"):
+    wl = wk.Workload("t", M, K, N, S, max(1, K // 100), kind, 0.02, seed)
+    return wk.make_case(wl)
+
+
+# --------------------------------------------------------------------------------------
+SHAPES = [  # M, K, S : several workgroup sizes, lanes-per-row tails, blocks-per-lane 1..4, S = 0 and S = K
+    (1, 16, 0), (3, 16, 16), (5, 48, 16), (16, 512, 32), (7, 1040, 0), (33, 1040, 1040), (67, 4096, 256),
+    (9, 5120, 512), (5, 14336, 256), (4, 16400, 4800), (3, 28672, 1024), (2, 40000, 16), (2, 65536, 2048),
+]
+
+
+@pytest.mark.parametrize("M,K,S", SHAPES)
+def test_quantize_act_bit_exact(M, K, S):
+    say(f"quantize_act parity M={M} K={K} S={S}")
+    c = rand_case(M, K, 8, S, seed=100 + K % 97)
+    want_c, want_s = A.quantize_act(c["X"], c["perm"], S, c["sT_x"])
+    got_c, got_s = gpu_quantize(B.arcq_quantize_act, c["X"], c["perm"], S, c["sT_x"])
+    assert_same_bytes(got_s, want_s, "scales")
+    assert_same_bytes(got_c, want_c, "codes")
+
+
+@pytest.mark.parametrize("N,K,S", [(1, 16, 16), (40, 512, 32), (300, 4096, 256), (17, 14336, 256), (5, 28672, 1024)])
+def test_pack_weight_bit_exact(N, K, S):
+    say(f"pack_weight parity N={N} K={K} S={S}")
+    wl = wk.Workload("t", 4, K, N, S, max(1, K // 100), "const50", 0.02, 200 + N)
+    c = wk.make_case(wl)
+    want_c, want_s = A.pack_weight(c["W"], c["perm"], S, c["sT_w"])
+    got_c, got_s = gpu_quantize(B.arcq_pack_weight, c["W"], c["perm"], S, c["sT_w"])
+    assert_same_bytes(got_s, want_s, "scales")
+    assert_same_bytes(got_c, want_c, "codes")
+
+
+def test_quantize_every_fp16_value_and_edge_blocks():
+    """All 63488 finite fp16 bit patterns (incl. +-0 and subnormals), shuffled into blocks, under
+    several tensor scales including ones that saturate the block scale; S = K so that every block
+    also goes through the residual stage."""
+    say("quantize_act parity over every finite fp16 value")
+    bits = np.arange(0x10000, dtype=np.uint32)
+    bits = bits[(bits & 0x7C00) != 0x7C00].astype(np.uint16)            # drop Inf/NaN
+    rng = np.random.default_rng(5)
+    vals = bits.view(np.float16)
+    K = 512
+    rows = []
+    for rep in range(3):
+        v = vals[rng.permutation(len(vals))]
+        rows.append(v[: len(v) // K * K].reshape(-1, K))
+    srt = np.sort(vals.astype(np.float32)).astype(np.float16)             # similar magnitudes share a block
+    rows.append(srt[: len(srt) // K * K].reshape(-1, K))
+    # exact grid midpoints times power-of-two scales: ties in the element rounding
+    mids = np.float16([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, 6.0])
+    tie = np.concatenate([mids * np.float16(2.0 ** e) * sgn for e in range(-8, 8) for sgn in (1, -1)])
+    tie = np.resize(tie, (4, K)).astype(np.float16)
+    tie[:, ::16] = (6.0 * 2.0 ** np.clip(np.arange(-8, 24), -8, 13)).astype(np.float16)[None, :]
+    rows.append(tie)
+    rows.append(np.zeros((2, K), np.float16))
+    rows[-1][1, ::3] = np.float16(-0.0)
+    X = np.concatenate(rows).astype(np.float16)
+    perm = rng.permutation(K).astype(np.int32)
+    for sT in (wk.tensor_scale(X), np.float32(1.0), np.float32(2.0 ** -12), np.float32(0.37), np.float32(3.1e-5)):
+        want_c, want_s = A.quantize_act(X, perm, K, sT)
+        got_c, got_s = gpu_quantize(B.arcq_quantize_act, X, perm, K, sT)
+        assert_same_bytes(got_s, want_s, f"scales sT={sT}")
+        assert_same_bytes(got_c, want_c, f"codes sT={sT}")
+
+
+def test_quantize_strided_input_and_determinism():
+    say("quantize_act with ldx > K, repeated")
+    c = rand_case(37, 1024, 8, 64, seed=9)
+    X, perm, S, sT = c["X"], c["perm"], c["S"], c["sT_x"]
+    wide = torch.full((37, 1024 + 24), 7.0, dtype=torch.float16, device="cuda")
+    wide[:, :1024] = dev(X)
+    want_c, want_s = A.quantize_act(X, perm, S, sT)
+    outs = []
+    for _ in range(2):
+        cc, ss = B.arcq_quantize_act(wide[:, :1024], dev(perm), S, sT)
+        outs.append((cc.cpu().numpy(), ss.cpu().numpy()))
+    assert_same_bytes(outs[0][0], want_c, "codes")
+    assert_same_bytes(outs[0][1], want_s, "scales")
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_empty_inputs_and_check_perm():
+    say("empty inputs, perm check")
+    perm = dev(np.arange(64, dtype=np.int32))
+    cc, ss = B.arcq_quantize_act(torch.empty((0, 64), dtype=torch.float16, device="cuda"), perm, 16, 1.0)
+    assert cc.shape == (0, 40) and ss.shape == (0, 5)
+    y = B.arcq_gemm(cc, ss, 1.0, torch.zeros((8, 40), dtype=torch.uint8, device="cuda"),
+                    torch.zeros((8, 5), dtype=torch.uint8, device="cuda"), 1.0)
+    assert y.shape == (0, 8)
+    assert B.arcq_check_perm(perm)
+    bad = np.arange(64, dtype=np.int32)
+    bad[5] = 6
+    assert not B.arcq_check_perm(dev(bad))
+    bad[5] = 64
+    assert not B.arcq_check_perm(dev(bad))
+    bad[5] = -1
+    assert not B.arcq_check_perm(dev(bad))
+
+
+# --------------------------------------------------------------------------------------
+GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny and skinny cases
+    (1, 1, 16, 0), (16, 512, 512, 32), (77, 200, 48, 16), (130, 129, 96, 16), (128, 256, 256, 0),
+    (257, 131, 1040, 48), (16, 1000, 4096, 256), (300, 77, 2048, 2048),
+]
+
+
+@pytest.mark.parametrize("M,N,K,S", GEMM_SHAPES)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+def test_gemm_parity(M, N, K, S, dtype):
+    say(f"gemm parity M={M} N={N} K={K} S={S} {dtype}")
+    c = rand_case(M, K, N, S, seed=300 + M + N)
+    ac, asc = A.quantize_act(c["X"], c["perm"], S, c["sT_x"])
+    wc, wsc = A.pack_weight(c["W"], c["perm"], S, c["sT_w"])
+    Yref = A.gemm(ac, asc, c["sT_x"], wc, wsc, c["sT_w"])
+    Y = B.arcq_gemm(dev(ac), dev(asc), c["sT_x"], dev(wc), dev(wsc), c["sT_w"], out_dtype=dtype)
+    torch.cuda.synchronize()
+    err = norm_err(Y.float().cpu().numpy(), Yref)
+    say(f"   normalised max error {err:.3e}")
+    assert err <= (GEMM_TOL_F16 if dtype == torch.float16 else GEMM_TOL_F32)
+
+
+def test_gemm_extreme_scales_and_codes():
+    """Largest and smallest scale bytes and every code value: the decode must be exact."""
+    say("gemm with extreme scale bytes")
+    rng = np.random.default_rng(17)
+    M, N, Kp = 64, 96, 128
+    ac = rng.integers(0, 256, (M, Kp // 2), dtype=np.uint8)
+    wc = rng.integers(0, 256, (N, Kp // 2), dtype=np.uint8)
+    asc = rng.choice(np.array([0, 1, 7, 8, 9, 0x38, 0x77, 0x7D, 0x7E], dtype=np.uint8), (M, Kp // 16))
+    wsc = rng.choice(np.array([0, 1, 2, 8, 0x40, 0x7E], dtype=np.uint8), (N, Kp // 16))
+    Yref = A.gemm(ac, asc, np.float32(1.0), wc, wsc, np.float32(1.0))
+    Y = B.arcq_gemm(dev(ac), dev(asc), 1.0, dev(wc), dev(wsc), 1.0, out_dtype=torch.float32)
+    assert norm_err(Y.cpu().numpy(), Yref) <= GEMM_TOL_F32
+    # a single non-zero product per output: the result must be exact in fp32
+    ac1 = np.zeros_like(ac); wc1 = np.zeros_like(wc)
+    ac1[:, 0] = 0x0F & rng.integers(1, 16, M, dtype=np.uint8)
+    wc1[:, 0] = 0x0F & rng.integers(1, 16, N, dtype=np.uint8)
+    Yref = A.gemm(ac1, asc, np.float32(1.0), wc1, wsc, np.float32(1.0))
+    Y = B.arcq_gemm(dev(ac1), dev(asc), 1.0, dev(wc1), dev(wsc), 1.0, out_dtype=torch.float32)
+    assert np.array_equal(Y.cpu().numpy().astype(np.float64), Yref)
+
+
+def test_gemm_strided_output_and_guard():
+    say("gemm with ldy > N")
+    c = rand_case(70, 256, 90, 32, seed=31)
+    ac, asc = A.quantize_act(c["X"], c["perm"], 32, c["sT_x"])
+    wc, wsc = A.pack_weight(c["W"], c["perm"], 32, c["sT_w"])
+    Yref = A.gemm(ac, asc, c["sT_x"], wc, wsc, c["sT_w"])
+    big = torch.full((70, 120), -77.0, dtype=torch.float32, device="cuda")
+    B.arcq_gemm(dev(ac), dev(asc), c["sT_x"], dev(wc), dev(wsc), c["sT_w"], y=big[:, :90])
+    out = big.cpu().numpy()
+    assert np.all(out[:, 90:] == -77.0)
+    assert norm_err(out[:, :90], Yref) <= GEMM_TOL_F32
+
+
+# --------------------------------------------------------------------------------------
+def run_full_config(name, sample_rows, sample_cols, full_quant):
+    """The whole hot path at a configuration's full size, as the benchmark launches it; the oracle
+    checks all of it where it can finish in seconds, otherwise sampled rows of X / W and the
+    corresponding entries of Y."""
+    wl = wk.WORKLOADS[name]
+    say(f"full config {name}: M={wl.M} K={wl.K} N={wl.N} S={wl.S}")
+    c = wk.make_case(wl)
+    X, W, perm, S = c["X"], c["W"], c["perm"], c["S"]
+    permd = dev(perm)
+    say("   gpu: quantize_act, pack_weight, gemm")
+    ac, asc = B.arcq_quantize_act(dev(X), permd, S, c["sT_x"])
+    wc, wsc = B.arcq_pack_weight(dev(W), permd, S, c["sT_w"])
+    Y = B.arcq_gemm(ac, asc, c["sT_x"], wc, wsc, c["sT_w"], out_dtype=torch.float16)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(wl.seed)
+    rows = np.arange(wl.M) if full_quant else np.sort(rng.choice(wl.M, min(sample_rows, wl.M), replace=False))
+    cols = np.arange(wl.N) if full_quant else np.sort(rng.choice(wl.N, min(sample_cols, wl.N), replace=False))
+    say(f"   oracle: {len(rows)} rows of X, {len(cols)} rows of W")
+    oac, oasc = A.quantize_act(X[rows], perm, S, c["sT_x"])
+    owc, owsc = [], []
+    for i in range(0, len(cols), 512):                   # chunked: the oracle's temporaries are 8x fp64
+        cc, ss = A.pack_weight(W[cols[i:i + 512]], perm, S, c["sT_w"])
+        owc.append(cc); owsc.append(ss)
+    owc, owsc = np.concatenate(owc), np.concatenate(owsc)
+    assert_same_bytes(asc.cpu().numpy()[rows], oasc, "activation scales")
+    assert_same_bytes(ac.cpu().numpy()[rows], oac, "activation codes")
+    assert_same_bytes(wsc.cpu().numpy()[cols], owsc, "weight scales")
+    assert_same_bytes(wc.cpu().numpy()[cols], owc, "weight codes")
+    Yref = A.gemm(oac, oasc, c["sT_x"], owc, owsc, c["sT_w"])
+    Yg = Y.cpu().numpy()[np.ix_(rows, cols)]
+    err = norm_err(Yg, Yref)
+    say(f"   gemm normalised max error {err:.3e}")
+    assert err <= GEMM_TOL_F16
+
+
+def test_config1_tiny_full():
+    run_full_config("c1_tiny", 0, 0, True)
+
+
+def test_config2_llama8b_qproj_full():
+    run_full_config("c2_llama8b_q", 0, 0, True)
+
+
+def test_config3_llama8b_mlp_decode_full():
+    run_full_config("c3a_llama8b_up", 16, 2048, False)
+    run_full_config("c3b_llama8b_down", 16, 1024, False)
+
+
+def test_config4_qwen32b_mlp_sampled():
+    run_full_config("c4_qwen32b_mlp", 96, 1024, False)
+
+
+def test_config5_llama70b_down_sampled():
+    run_full_config("c5_llama70b_down", 48, 384, False)

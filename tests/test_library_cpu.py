@@ -1,0 +1,98 @@
+"""No-GPU checks of the C-ABI library: it loads, exports every declared symbol, and rejects
+bad arguments before any HIP call (so these run on a machine without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2601_07475_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "arcq.h")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(B.LIB_PATH), reason="libarcq.so not built")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(arcq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = declared_symbols()
+    assert "arcq_quantize_act" in names and "arcq_pack_weight" in names and "arcq_gemm" in names
+    handle = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(handle, n), n
+    assert sorted(B.SIGNATURES) == names
+    assert B.arcq_version() >= 100
+
+
+def test_packed_sizes():
+    assert B.arcq_packed_sizes(16, 512, 32) == (16 * 544 // 2, 16 * 544 // 16)
+    assert B.arcq_packed_sizes(0, 512, 0) == (0, 0)
+    for K, S in ((0, 0), (24, 0), (512, 8), (512, 528), (512, -16), (B.MAX_K + 16, 0)):
+        with pytest.raises(B.ArcqError) as e:
+            B.arcq_packed_sizes(4, K, S)
+        assert e.value.status == B.BAD_SHAPE
+
+
+FAKE = ctypes.c_void_p(0x10000)       # never dereferenced: every call below must fail validation first
+ODD = ctypes.c_void_p(0x10004)
+
+
+def q(fn, x=FAKE, rows=4, K=512, ld=512, perm=FAKE, S=32, sT=1.0, codes=FAKE, scales=FAKE):
+    return getattr(B.lib(), fn)(x, rows, K, ld, perm, S, sT, codes, scales, None)
+
+
+@pytest.mark.parametrize("fn", ["arcq_quantize_act", "arcq_pack_weight"])
+def test_quantizer_argument_errors(fn):
+    assert q(fn, K=500) == B.BAD_SHAPE
+    assert q(fn, S=24) == B.BAD_SHAPE
+    assert q(fn, S=1024) == B.BAD_SHAPE
+    assert q(fn, rows=-1) == B.BAD_SHAPE
+    assert q(fn, ld=496) == B.BAD_SHAPE
+    assert q(fn, K=B.MAX_K + 16, ld=B.MAX_K + 16) == B.BAD_SHAPE
+    for bad in (0.0, -1.0, float("inf"), float("nan"), 2.0 ** -70, 2.0 ** 70):
+        assert q(fn, sT=bad) == B.INVALID_ARG
+    assert q(fn, x=None) == B.INVALID_ARG
+    assert q(fn, perm=None) == B.INVALID_ARG
+    assert q(fn, codes=None) == B.INVALID_ARG
+    assert q(fn, scales=None) == B.INVALID_ARG
+    assert q(fn, x=ODD) == B.BAD_ALIGN
+    assert q(fn, ld=516) == B.BAD_ALIGN
+    assert q(fn, codes=ODD) == B.BAD_ALIGN
+    assert b"aligned" in B.lib().arcq_last_error()
+    assert q(fn, rows=0, x=None, perm=None, codes=None, scales=None) == B.OK      # empty input: nothing to do
+    assert B.lib().arcq_last_error() == b""
+
+
+def g(ac=FAKE, asc=FAKE, sa=1.0, wc=FAKE, wsc=FAKE, sw=1.0, M=4, N=8, Kp=64, y=FAKE, dt=0, ldy=8, ws=None, wsb=0):
+    return B.lib().arcq_gemm(ac, asc, sa, wc, wsc, sw, M, N, Kp, y, dt, ldy, ws, wsb, None)
+
+
+def test_gemm_argument_errors():
+    assert g(Kp=0) == B.BAD_SHAPE
+    assert g(Kp=40) == B.BAD_SHAPE
+    assert g(M=-1) == B.BAD_SHAPE
+    assert g(ldy=4) == B.BAD_SHAPE
+    assert g(dt=7) == B.INVALID_ARG
+    assert g(sa=0.0) == B.INVALID_ARG
+    assert g(sw=float("nan")) == B.INVALID_ARG
+    assert g(ac=None) == B.INVALID_ARG
+    assert g(y=None) == B.INVALID_ARG
+    assert g(wc=ODD) == B.BAD_ALIGN
+    assert g(y=ctypes.c_void_p(0x10002)) == B.BAD_ALIGN
+    assert g(M=0, ac=None, asc=None, y=None) == B.OK
+    assert g(N=0, wc=None, wsc=None, y=None) == B.OK
+    n = ctypes.c_size_t(123)
+    assert B.lib().arcq_gemm_workspace_size(4, 8, 64, ctypes.byref(n)) == B.OK
+    assert B.lib().arcq_gemm_workspace_size(4, 8, 40, ctypes.byref(n)) == B.BAD_SHAPE
+
+
+def test_check_perm_argument_errors():
+    r = ctypes.c_int(0)
+    assert B.lib().arcq_check_perm(None, 16, FAKE, ctypes.byref(r), None) == B.INVALID_ARG
+    assert B.lib().arcq_check_perm(FAKE, 0, FAKE, ctypes.byref(r), None) == B.BAD_SHAPE
