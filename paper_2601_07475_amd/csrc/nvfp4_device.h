@@ -34,24 +34,14 @@ __device__ __forceinline__ float e4m3_decode(uint32_t b) {
     return b < 8u ? sub : nor;
 }
 
-// Index 0..7 of the E2M1 magnitude nearest to w >= 0; ties to the even index; w > 6 -> 6.
-// Midpoints 0.25 .75 1.25 1.75 2.5 3.5 5: the tie goes down when the lower neighbour is even.
-__device__ __forceinline__ uint32_t e2m1_encode_mag(float w) {
-    return (uint32_t)(w > 0.25f) + (uint32_t)(w >= 0.75f) + (uint32_t)(w > 1.25f) +
-           (uint32_t)(w >= 1.75f) + (uint32_t)(w > 2.5f) + (uint32_t)(w >= 3.5f) +
-           (uint32_t)(w > 5.0f);
-}
-
-// E2M1 magnitude of index 0..7 as fp32.
-__device__ __forceinline__ float e2m1_mag(uint32_t idx) {
-    float sub = 0.5f * (float)idx;                                // 0, 0.5
-    float nor = __uint_as_float((idx << 22) + 0x3F000000u);       // (1 + m/2) * 2^(e-1)
-    return idx < 2u ? sub : nor;
-}
-
 // Quantize one block of 16 fp32 values.  Outputs the scale byte, the effective scale
 // s = E4M3value * s_T, and the 16 codes packed low-nibble-first into lo (elements 0..7)
 // and hi (elements 8..15).
+//
+// The element rounding uses v_cvt_scalef32_pk_fp4_f32 with scale 1.0: two fp32 -> two E2M1
+// codes in one byte (first operand in the low nibble), round-to-nearest-even on the E2M1
+// grid, saturating at +-6, sign bit kept for zeros.  The signed quotient v * inv is fed
+// directly: rounding is symmetric, so this equals sign | round(|v| * inv).
 __device__ __forceinline__ void quantize_block16(const float (&v)[16], float s_T, float ginv,
                                                  uint32_t& sbyte, float& s,
                                                  uint32_t& lo, uint32_t& hi) {
@@ -64,26 +54,34 @@ __device__ __forceinline__ void quantize_block16(const float (&v)[16], float s_T
     float inv = (s != 0.0f) ? 1.0f / s : 0.0f;
     lo = 0u;
     hi = 0u;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        float w = fabsf(v[i]) * inv;
-        uint32_t code = e2m1_encode_mag(w) | ((__float_as_uint(v[i]) >> 28) & 8u);
-        if (i < 8) lo |= code << (4 * i);
-        else       hi |= code << (4 * (i - 8));
-    }
+    lo = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(lo, v[0] * inv, v[1] * inv, 1.0f, 0);
+    lo = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(lo, v[2] * inv, v[3] * inv, 1.0f, 1);
+    lo = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(lo, v[4] * inv, v[5] * inv, 1.0f, 2);
+    lo = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(lo, v[6] * inv, v[7] * inv, 1.0f, 3);
+    hi = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(hi, v[8] * inv, v[9] * inv, 1.0f, 0);
+    hi = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(hi, v[10] * inv, v[11] * inv, 1.0f, 1);
+    hi = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(hi, v[12] * inv, v[13] * inv, 1.0f, 2);
+    hi = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(hi, v[14] * inv, v[15] * inv, 1.0f, 3);
 }
 
+typedef float float2v __attribute__((ext_vector_type(2)));
+
 // Residual of one block: r_i = fma(-G[code_i] * sign_i, s, v_i), one rounding
-// (Section 3.2 step (2): R_o = X_o - s * Q_{X_o}).
+// (Section 3.2 step (2): R_o = X_o - s * Q_{X_o}).  v_cvt_scalef32_pk_f32_fp4 with scale 1.0
+// returns the two signed grid values of one byte (low nibble first).
 __device__ __forceinline__ void residual_block16(const float (&v)[16], float s,
                                                  uint32_t lo, uint32_t hi, float (&r)[16]) {
+    float2v g[8];
+    g[0] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(lo, 1.0f, 0);
+    g[1] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(lo, 1.0f, 1);
+    g[2] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(lo, 1.0f, 2);
+    g[3] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(lo, 1.0f, 3);
+    g[4] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(hi, 1.0f, 0);
+    g[5] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(hi, 1.0f, 1);
+    g[6] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(hi, 1.0f, 2);
+    g[7] = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(hi, 1.0f, 3);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        uint32_t code = ((i < 8 ? lo : hi) >> (4 * (i & 7))) & 0xFu;
-        float g = e2m1_mag(code & 7u);
-        float gs = __uint_as_float(__float_as_uint(g) | ((code & 8u) << 28));
-        r[i] = __builtin_fmaf(-gs, s, v[i]);
-    }
+    for (int i = 0; i < 16; ++i) r[i] = __builtin_fmaf(-g[i >> 1][i & 1], s, v[i]);
 }
 
 }  // namespace arcq
