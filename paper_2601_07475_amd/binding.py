@@ -10,7 +10,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libarcq.so")
+LIB_PATH = os.environ.get("ARCQ_LIBRARY") or os.path.join(_HERE, "libarcq.so")   # override: a differently built copy
 
 OK, INVALID_ARG, BAD_SHAPE, BAD_ALIGN, HIP_ERROR, WORKSPACE_TOO_SMALL = range(6)
 DTYPE_F16, DTYPE_F32 = 0, 1

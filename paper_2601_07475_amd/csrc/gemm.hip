@@ -206,71 +206,59 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(
     const int wg_m0 = tile_m * C::BM, wg_n0 = tile_n * C::BN;
     const int wrow0 = (wave >> 1) * (32 * WM);       // first row of this wave inside the A tile
     const int wcol0 = (wave & 1) * (32 * WN);        // first row of this wave inside the W tile
-    const int64_t cpitch = (int64_t)nbk * 8, spitch = nbk;
 
-    // ---- DMA source offsets of this thread (bytes from the operand base, stage 0)
+    // ---- DMA source offsets of this thread (bytes from the operand base)
     // When K' is an odd multiple of 64 the last stage is half a stage (4 blocks): the lanes that
     // would fetch its missing second half re-fetch the first half instead (never used), which
     // keeps every access inside the operand.  `half` selects those adjusted offsets.
     const bool has_half = (nbk & 7) != 0;
     const int nstage = (nbk >> 3) + (has_half ? 1 : 0);
-    uint32_t src_ac[C::BM / 64], src_wc[C::BN / 64], src_as[C::BM / 128], src_ws[C::BN / 128];
-    uint32_t adj_c[2], adj_s;                  // (s & 3) and the row swizzle repeat every 256 slots
-    {
-        const int row = tid >> 2, lp = (tid & 3) ^ ((row >> 1) & 3);
-        adj_c[0] = lp * 16;
-        adj_c[1] = (lp & 1) * 16;
-        adj_s = (tid & 1) * 4;
-    }
-#pragma unroll
-    for (int p = 0; p < C::BM / 64; ++p)
-        src_ac[p] = (uint32_t)(min(wg_m0 + ((p * 256 + tid) >> 2), M - 1) * cpitch);
-#pragma unroll
-    for (int p = 0; p < C::BN / 64; ++p)
-        src_wc[p] = (uint32_t)(min(wg_n0 + ((p * 256 + tid) >> 2), N - 1) * cpitch);
-#pragma unroll
-    for (int p = 0; p < C::BM / 128; ++p)
-        src_as[p] = (uint32_t)(min(wg_m0 + ((p * 256 + tid) >> 1), M - 1) * spitch);
-#pragma unroll
-    for (int p = 0; p < C::BN / 128; ++p)
-        src_ws[p] = (uint32_t)(min(wg_n0 + ((p * 256 + tid) >> 1), N - 1) * spitch);
+    // Offsets are recomputed per copy (a handful of ALU operations per stage) rather than kept
+    // in registers: the accumulators leave this kernel 256 registers and it needs most of them.
+    // (s & 3) and the row swizzle repeat every 256 slots, so one value serves every copy
+    const uint32_t lp_ = (uint32_t)((tid & 3) ^ ((tid >> 3) & 3));
+    const uint32_t adj_c0 = lp_ * 16u, adj_c1 = (lp_ & 1u) * 16u, adj_s = (uint32_t)(tid & 1) * 4u;
+    const int crow = tid >> 2, srow = tid >> 1; // row of this thread inside a 64-row / 128-row copy
+    const uint32_t cpitch32 = (uint32_t)nbk * 8u, spitch32 = (uint32_t)nbk;
     const uint32_t wave_slot = (uint32_t)(tid & ~63);   // lane l of a DMA writes slot wave_slot + l
     const uint32_t lds0 = lds_address(lds);
-    auto issue = [&](int stage, int buf) {
+    // DMA instruction d (0 .. NDMA-1) of a stage: A code pieces, W code pieces, A scales, W scales.
+    auto issue_one = [&](int d, int stage, int buf) {
         const uint32_t base = lds0 + buf * C::STAGE_BYTES;
         const bool half = has_half && stage == nstage - 1;
-        const uint32_t oc = (uint32_t)stage * 64u + (half ? adj_c[1] : adj_c[0]);
+        const uint32_t oc = (uint32_t)stage * 64u + (half ? adj_c1 : adj_c0);
         const uint32_t os = (uint32_t)stage * 8u + (half ? 0u : adj_s);
+        constexpr int NA = C::BM / 64, NW = C::BN / 64, NAS = C::BM / 128;
+        // rows past the edge of the operand re-read its last row (never stored)
+        if (d < NA) {
+            const uint32_t row = (uint32_t)min(wg_m0 + d * 64 + crow, M - 1);
+            dma16(a_codes, row * cpitch32 + oc, base + C::A_CODES + 16u * (d * 256 + wave_slot));
+        } else if (d < NA + NW) {
+            const int p = d - NA;
+            const uint32_t row = (uint32_t)min(wg_n0 + p * 64 + crow, N - 1);
+            dma16(w_codes, row * cpitch32 + oc, base + C::W_CODES + 16u * (p * 256 + wave_slot));
+        } else if (d < NA + NW + NAS) {
+            const int p = d - NA - NW;
+            const uint32_t row = (uint32_t)min(wg_m0 + p * 128 + srow, M - 1);
+            dma4(a_scales, row * spitch32 + os, base + C::A_SCALES + 4u * (p * 256 + wave_slot));
+        } else {
+            const int p = d - NA - NW - NAS;
+            const uint32_t row = (uint32_t)min(wg_n0 + p * 128 + srow, N - 1);
+            dma4(w_scales, row * spitch32 + os, base + C::W_SCALES + 4u * (p * 256 + wave_slot));
+        }
+    };
+    auto issue_all = [&](int stage, int buf) {
 #pragma unroll
-        for (int p = 0; p < C::BM / 64; ++p)
-            dma16(a_codes, src_ac[p] + oc, base + C::A_CODES + 16u * (p * 256 + wave_slot));
-#pragma unroll
-        for (int p = 0; p < C::BN / 64; ++p)
-            dma16(w_codes, src_wc[p] + oc, base + C::W_CODES + 16u * (p * 256 + wave_slot));
-#pragma unroll
-        for (int p = 0; p < C::BM / 128; ++p)
-            dma4(a_scales, src_as[p] + os, base + C::A_SCALES + 4u * (p * 256 + wave_slot));
-#pragma unroll
-        for (int p = 0; p < C::BN / 128; ++p)
-            dma4(w_scales, src_ws[p] + os, base + C::W_SCALES + 4u * (p * 256 + wave_slot));
+        for (int d = 0; d < C::NDMA; ++d) issue_one(d, stage, buf);
     };
 
-    // ---- LDS read offsets of this lane inside a stage (piece index still to be swizzled)
-    uint32_t rd_ac[WM], rd_wc[WN], rd_as[WM], rd_ws[WN], sw_a[WM], sw_w[WN];
-#pragma unroll
-    for (int i = 0; i < WM; ++i) {
-        const int row = wrow0 + 32 * i + r;
-        rd_ac[i] = C::A_CODES + row * 64;
-        rd_as[i] = C::A_SCALES + row * 8 + 2 * h;
-        sw_a[i] = (row >> 1) & 3;
-    }
-#pragma unroll
-    for (int j = 0; j < WN; ++j) {
-        const int row = wcol0 + 32 * j + r;
-        rd_wc[j] = C::W_CODES + row * 64;
-        rd_ws[j] = C::W_SCALES + row * 8 + 2 * h;
-        sw_w[j] = (row >> 1) & 3;
-    }
+    // ---- LDS read offsets of this lane inside a stage.  Fragment i of a wave is 32 rows (2048
+    // bytes of codes, 256 of scales) further on, a constant folded into the instruction; the
+    // swizzle (row >> 1) & 3 only depends on lane % 32 because the other terms are multiples of 32.
+    const uint32_t swz = (uint32_t)(r >> 1) & 3u;
+    const uint32_t rd_a = C::A_CODES + (wrow0 + r) * 64, rd_w = C::W_CODES + (wcol0 + r) * 64;
+    const uint32_t rd_as = C::A_SCALES + (wrow0 + r) * 8 + 2 * h, rd_ws = C::W_SCALES + (wcol0 + r) * 8 + 2 * h;
+    const uint32_t piece0 = 16u * ((uint32_t)h ^ swz), piece1 = 16u * ((2u + (uint32_t)h) ^ swz);
 
     float16v acc[WM][WN];
 #pragma unroll
@@ -280,29 +268,36 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    // ---- per-stage compute, software-pipelined by hand.
+    // ---- per-stage compute, software-pipelined by hand (one wave per SIMD: nothing else hides
+    // a stall, so every wait is placed where its data has long been ready).
     // A k-step (one block, 16 k) is WM*WN MFMAs fed by WM + WN fragments of 8 fp16 per lane.
     // While the MFMAs of step x run, the fragments of step x+1 are decoded: after every pair of
     // MFMAs the decode of one (or two) fragments is placed, and scheduling barriers keep the
-    // compiler from regrouping them, so the matrix pipe (32 clocks per MFMA) stays busy while
-    // the vector ALU decodes.  Raw codes for the second half of a stage are read from LDS
-    // during the first k-step.
+    // compiler from regrouping them, so the matrix pipe stays busy while the vector ALU decodes.
+    // The pipeline runs ACROSS stages: the barrier that opens stage s+1 sits before step 6 of
+    // stage s; step 6 reads the first raw codes of stage s+1 from LDS and step 7 decodes its
+    // first fragments.  The copies for stage s+2 are issued two per k-step during steps 0-5 of
+    // stage s (its buffer was last read in stage s-1, which every wave left before the barrier
+    // that opened stage s), so no wave ever queues a burst of memory instructions.
     constexpr int G = WM + WN;                 // fragments per k-step
     constexpr int P = (WM * WN) / 2;           // MFMA pairs per k-step
     uint4 ca[2][WM], cw[2][WN];
     uint32_t sa[2][WM], sw[2][WN];
     half8 fa[2][WM], fw[2][WN];
-    const uint8_t* st = lds;
-    auto read_raw = [&](int u) {
+    auto read_raw = [&](int u, const uint8_t* st) {
+        const uint8_t* pa = st + rd_a + (u ? piece1 : piece0);
+        const uint8_t* pw = st + rd_w + (u ? piece1 : piece0);
+        const uint8_t* psa = st + rd_as + 4 * u;
+        const uint8_t* psw = st + rd_ws + 4 * u;
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
-            ca[u][i] = *reinterpret_cast<const uint4*>(st + rd_ac[i] + 16u * ((2 * u + h) ^ sw_a[i]));
-            sa[u][i] = *reinterpret_cast<const uint16_t*>(st + rd_as[i] + 4 * u);
+            ca[u][i] = *reinterpret_cast<const uint4*>(pa + i * 2048);
+            sa[u][i] = *reinterpret_cast<const uint16_t*>(psa + i * 256);
         }
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
-            cw[u][j] = *reinterpret_cast<const uint4*>(st + rd_wc[j] + 16u * ((2 * u + h) ^ sw_w[j]));
-            sw[u][j] = *reinterpret_cast<const uint16_t*>(st + rd_ws[j] + 4 * u);
+            cw[u][j] = *reinterpret_cast<const uint4*>(pw + j * 2048);
+            sw[u][j] = *reinterpret_cast<const uint16_t*>(psw + j * 256);
         }
     };
     auto decode_frag = [&](int gidx, int x) {   // fragment gidx of k-step x (0..7) into slot x & 1
@@ -319,30 +314,34 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(
         }
     };
 
-    // One stage: wait for its copies, open it with a barrier, start the copies two stages ahead,
-    // then NSTEPS k-steps (8, or 4 for the half stage that ends an odd multiple of 64).
-    int buf = 0;
+    // The steady-state stage is free of branches (they would split the hand-made schedule):
+    // past the end of K' it keeps issuing copies (of the last stage, into a free ring slot) and
+    // keeps reading and decoding a "next" stage whose values are never used.
+    int buf = 0;                                // ring slot of the stage being computed
+    auto ring_next = [](int b) { return b == 2 ? 0 : b + 1; };
     auto run_stage = [&](int s, auto nsteps_tag) {
         constexpr int NSTEPS = decltype(nsteps_tag)::value;
-        // vector-memory operations retire in issue order: at most NDMA outstanding means
-        // everything older than the youngest stage has landed
-        if (s + 1 < nstage) wait_vmcnt<C::NDMA>();
-        else wait_vmcnt<0>();
-        wg_barrier();
-        if (s + 2 < nstage) issue(s + 2, buf >= 1 ? buf - 1 : 2);     // (buf + 2) % 3
-        st = lds + buf * C::STAGE_BYTES;
-        read_raw(0);
-#pragma unroll
-        for (int gidx = 0; gidx < G; ++gidx) decode_frag(gidx, 0);
-        if (NSTEPS > 4) read_raw(1);
-        __builtin_amdgcn_sched_barrier(0);
+        constexpr bool FULL = NSTEPS == 8;      // a half stage is always the last one
+        const uint8_t* st = lds + buf * C::STAGE_BYTES;
+        const int buf1 = ring_next(buf), buf2 = ring_next(buf1);
+        const int fetch = min(s + 2, nstage - 1);
 #pragma unroll
         for (int x = 0; x < NSTEPS; ++x) {
+            if (x == 0 && FULL) read_raw(1, st);
+            if (x == 6) {
+                // stage s+1 must have landed: everything but the NDMA copies issued during steps
+                // 0-5 (younger) has retired once at most NDMA operations are outstanding
+                wait_vmcnt<C::NDMA>();
+                wg_barrier();
+                read_raw(0, lds + buf1 * C::STAGE_BYTES);
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int p = 0; p < P; ++p) {
-                if (x + 1 < NSTEPS) {
 #pragma unroll
-                    for (int gidx = (p * G) / P; gidx < ((p + 1) * G) / P; ++gidx) decode_frag(gidx, x + 1);
+                for (int gidx = (p * G) / P; gidx < ((p + 1) * G) / P; ++gidx) {
+                    if (x + 1 < NSTEPS) decode_frag(gidx, x + 1);
+                    else if (FULL) decode_frag(gidx, 0);          // first step of stage s+1
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -351,16 +350,28 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[x & 1][i], fw[x & 1][j], acc[i][j], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
+                if (FULL && x < 6) {            // copies of stage s+2, spread over steps 0..5
+#pragma unroll
+                    for (int d = 0; d < C::NDMA; ++d)
+                        if ((d * 6) / C::NDMA == x && (d - (x * C::NDMA + 5) / 6) == p) issue_one(d, fetch, buf2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
-        buf = buf == 2 ? 0 : buf + 1;
+        buf = buf1;
     };
 
-    if (nstage > 0) issue(0, 0);
-    if (nstage > 1) issue(1, 1);
+    issue_all(0, 0);
+    issue_all(min(1, nstage - 1), 1);
+    wait_vmcnt<C::NDMA>();
+    wg_barrier();
+    read_raw(0, lds);
+#pragma unroll
+    for (int gidx = 0; gidx < G; ++gidx) decode_frag(gidx, 0);
     const int nfull = nbk >> 3;
     for (int s = 0; s < nfull; ++s) run_stage(s, std::integral_constant<int, 8>{});
     if (has_half) run_stage(nfull, std::integral_constant<int, 4>{});
+    wait_vmcnt<0>();                            // no copy may still be in flight when the LDS is released
 
     const int m0 = wg_m0 + wrow0, n0 = wg_n0 + wcol0;
     store_tile<WM, WN>(acc, m0, n0, r, h, M, N, alpha, y, ldy);
