@@ -392,11 +392,118 @@ arcq_status launch_staged(const uint8_t* a_codes, const uint8_t* a_scales, const
     return check_launch("gemm_staged_kernel");
 }
 
+// ---------------------------------------------------------------------------------------------
+// Skinny kernel for M <= 16 (decode): bound by streaming the packed weights once from HBM
+// (9/16 byte per weight), so the layout of the work follows the weight rows.
+//
+// v_mfma_f32_16x16x32_f16: lane (i = lane % 16, q = lane / 16) supplies 8 consecutive k of row i;
+// the four lane groups q supply different octets.  The activations are the 16-row operand, the
+// weights the 16-column operand.  A lane loads 16 bytes (32 codes, blocks 8c+2q and 8c+2q+1 of
+// chunk c = 128 k) of its weight row, which feed 4 MFMAs; the 16 rows of a tile make each wave
+// load 16 x 64 contiguous bytes.  A workgroup owns NT tiles of 16 weight rows; its waves split
+// K' (wave w takes chunks w, w + WAVES, ...), share nothing while streaming, and add their
+// partial 16 x 16 tiles through LDS at the end.  Rows of the activation operand past M repeat
+// row M-1 and are not stored.
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+template <int NT, int WAVES, typename OutT>
+__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
+    const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
+    const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N,
+    int nbk, float alpha, OutT* __restrict__ y, int64_t ldy) {
+    __shared__ float red[WAVES][NT][4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, q = lane >> 4;
+    const int n0 = blockIdx.x * (16 * NT);
+    const int64_t cpitch = (int64_t)nbk * 8, spitch = nbk;
+    const int nchunk = (nbk + 7) >> 3;                       // chunks of 8 blocks, the last may be partial
+
+    const uint8_t* ac = a_codes + (int64_t)min(i, M - 1) * cpitch + 16 * q;
+    const uint8_t* as = a_scales + (int64_t)min(i, M - 1) * spitch + 2 * q;
+    const uint8_t *wc[NT], *ws[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int n = min(n0 + 16 * t + i, N - 1);
+        wc[t] = w_codes + n * cpitch + 16 * q;
+        ws[t] = w_scales + n * spitch + 2 * q;
+    }
+    float4v acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    constexpr int U = 2;                                     // chunks in flight per wave
+    for (int c0 = wave * U; c0 < nchunk; c0 += WAVES * U) {
+        uint4 ca[U], cw[U][NT];
+        uint32_t sa[U], sw[U][NT];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + u;
+            // the lane's two blocks exist (nbk is even); otherwise they contribute zero
+            const bool ok = 8 * c + 2 * q < nbk;
+            const int cc = ok ? c : 0;
+            ca[u] = *reinterpret_cast<const uint4*>(ac + 64 * (int64_t)cc);
+            sa[u] = *reinterpret_cast<const uint16_t*>(as + 8 * (int64_t)cc);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                cw[u][t] = *reinterpret_cast<const uint4*>(wc[t] + 64 * (int64_t)cc);
+                sw[u][t] = *reinterpret_cast<const uint16_t*>(ws[t] + 8 * (int64_t)cc);
+            }
+            if (!ok) ca[u] = make_uint4(0, 0, 0, 0);        // zero activations are enough
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t a32 = k == 0 ? ca[u].x : k == 1 ? ca[u].y : k == 2 ? ca[u].z : ca[u].w;
+                const half8 fa = decode8(a32, scale_pair(k < 2 ? (sa[u] & 0xFFu) : (sa[u] >> 8)));
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const uint32_t w32 = k == 0 ? cw[u][t].x : k == 1 ? cw[u][t].y : k == 2 ? cw[u][t].z : cw[u][t].w;
+                    const half8 fw = decode8(w32, scale_pair(k < 2 ? (sw[u][t] & 0xFFu) : (sw[u][t] >> 8)));
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa, fw, acc[t], 0, 0, 0);
+                }
+            }
+    }
+    // D layout of the 16x16 MFMA: lane holds column (lane % 16); register e holds row 4 * (lane / 16) + e.
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) red[wave][t][e][lane] = acc[t][e];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < NT * 4 * 64; idx += WAVES * 64) {
+        const int t = idx >> 8, e = (idx >> 6) & 3, l = idx & 63;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) sum += red[w][t][e][l];
+        const int m = 4 * (l >> 4) + e, n = n0 + 16 * t + (l & 15);
+        if (m < M && n < N) store_out(y + (int64_t)m * ldy + n, sum * alpha);
+    }
+}
+
+template <int NT, int WAVES, typename OutT>
+arcq_status launch_skinny(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                          const uint8_t* w_scales, int M, int N, int nbk, float alpha, OutT* y, int64_t ldy,
+                          hipStream_t stream) {
+    const int grid = (N + 16 * NT - 1) / (16 * NT);
+    hipLaunchKernelGGL((gemm_skinny_kernel<NT, WAVES, OutT>), dim3(grid), dim3(WAVES * 64), 0, stream, a_codes,
+                       a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy);
+    return check_launch("gemm_skinny_kernel");
+}
+
 template <typename OutT>
 arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                          const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, float alpha, OutT* y,
                          int64_t ldy, hipStream_t stream) {
     const int nbk = (int)(Kp >> 4);
+    if (M <= 16 && (nbk & 1) == 0 &&
+        ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
+        ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 1) == 0) {
+        // enough waves to keep the weight stream in flight: split K' more when there are few rows
+        const int64_t tiles = (N + 31) / 32;
+        if (tiles * 8 >= 2048 || nbk < 128)
+            return launch_skinny<2, 8>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+        return launch_skinny<2, 16>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+    }
     const bool offsets_fit = (uint64_t)M * (uint64_t)nbk * 8 < 0xFFFF0000ull && (uint64_t)N * (uint64_t)nbk * 8 < 0xFFFF0000ull;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
                            ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 3) == 0;
