@@ -400,13 +400,19 @@ arcq_status launch_staged(const uint8_t* a_codes, const uint8_t* a_scales, const
 // the four lane groups q supply different octets.  The activations are the 16-row operand, the
 // weights the 16-column operand.  A lane loads 16 bytes (32 codes, blocks 8c+2q and 8c+2q+1 of
 // chunk c = 128 k) of its weight row, which feed 4 MFMAs; the 16 rows of a tile make each wave
-// load 16 x 64 contiguous bytes.  A workgroup owns NT tiles of 16 weight rows; its waves split
-// K' (wave w takes chunks w, w + WAVES, ...), share nothing while streaming, and add their
-// partial 16 x 16 tiles through LDS at the end.  Rows of the activation operand past M repeat
-// row M-1 and are not stored.
+// load 16 x 64 contiguous bytes.  Rows of the activation operand past M repeat row M-1 and are
+// not stored.
+//
+// Everything is loaded straight into registers, U chunks at a time, and latency is hidden by
+// occupancy (about 64 registers per lane, so more than twenty waves per CU) rather than by
+// prefetching: variants that staged the activations and scale bytes in LDS or double-buffered
+// the weight stream in registers measured 1.4-1.6x slower at the decode shapes.  Every wave
+// handles NT tiles of 16 weight rows for the same chunks, which shares the loads and the decode
+// of the activation operand; the WAVES waves of a workgroup split K' (wave w takes chunks
+// w*U .. w*U+U-1, then strides on) and add their partial tiles through LDS at the end.
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-template <int NT, int WAVES, typename OutT>
+template <int NT, int WAVES, int U, typename OutT>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N,
@@ -431,7 +437,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    constexpr int U = 2;                                     // chunks in flight per wave
     for (int c0 = wave * U; c0 < nchunk; c0 += WAVES * U) {
         uint4 ca[U], cw[U][NT];
         uint32_t sa[U], sw[U][NT];
@@ -464,7 +469,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
                 }
             }
     }
-    // D layout of the 16x16 MFMA: lane holds column (lane % 16); register e holds row 4 * (lane / 16) + e.
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -480,13 +484,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     }
 }
 
-template <int NT, int WAVES, typename OutT>
+template <int NT, int WAVES, int U, typename OutT>
 arcq_status launch_skinny(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
-                          const uint8_t* w_scales, int M, int N, int nbk, float alpha, OutT* y, int64_t ldy,
-                          hipStream_t stream) {
-    const int grid = (N + 16 * NT - 1) / (16 * NT);
-    hipLaunchKernelGGL((gemm_skinny_kernel<NT, WAVES, OutT>), dim3(grid), dim3(WAVES * 64), 0, stream, a_codes,
-                       a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy);
+                                 const uint8_t* w_scales, int M, int N, int nbk, float alpha, OutT* y, int64_t ldy,
+                                 hipStream_t stream) {
+    hipLaunchKernelGGL((gemm_skinny_kernel<NT, WAVES, U, OutT>), dim3((N + 16 * NT - 1) / (16 * NT)),
+                       dim3(WAVES * 64), 0, stream, a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy);
     return check_launch("gemm_skinny_kernel");
 }
 
@@ -498,11 +501,16 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
     if (M <= 16 && (nbk & 1) == 0 &&
         ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
         ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 1) == 0) {
-        // enough waves to keep the weight stream in flight: split K' more when there are few rows
-        const int64_t tiles = (N + 31) / 32;
-        if (tiles * 8 >= 2048 || nbk < 128)
-            return launch_skinny<2, 8>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
-        return launch_skinny<2, 16>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+        // enough waves to keep the weight stream in flight (>= 8 per CU), as few as that allows so
+        // that each wave has several KB to request at once
+        // many weight rows: several tiles per wave share the activation operand; few rows: one
+        // tile per wave so that every CU still gets a workgroup (measured at the decode shapes)
+        const int64_t tiles = (N + 15) / 16;
+        if (tiles >= 800)
+            return launch_skinny<4, 8, 1>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+        if (tiles >= 400)
+            return launch_skinny<2, 8, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+        return launch_skinny<1, 8, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
     }
     const bool offsets_fit = (uint64_t)M * (uint64_t)nbk * 8 < 0xFFFF0000ull && (uint64_t)N * (uint64_t)nbk * 8 < 0xFFFF0000ull;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&

@@ -48,6 +48,13 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("" ::: "memory");
 }
 
+// Waits for every outstanding LDS / scalar-memory operation of this wave (lgkmcnt(0)) only.
+__device__ __forceinline__ void wait_lgkmcnt0() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    asm volatile("" ::: "memory");
+}
+
 // Workgroup barrier without the memory fence of __syncthreads() (which would drain every
 // outstanding vector-memory operation, prefetches included).  Memory accesses are not moved
 // across it by the compiler.
