@@ -9,7 +9,9 @@ Weight Quantization").  The default workload is the LLaMA-3-8B q_proj prefill sh
 
 Prints ONE JSON line.  `value` = 2*M*N*K' / step time, in TFLOP/s.  `roofline` prices the dominant
 kernel (the GEMM; fp16 MFMA peak because operands are decoded exactly to fp16).  `cpu_baseline`
-is the numpy oracle timed on the host cores on the same workload.
+is the numpy oracle timed on the host cores on the same workload.  `also` holds the other
+single-GPU workloads (fewer steps): the HBM-streaming claim of the quantizer is made on
+c5_llama70b_down, the decode shapes c3a/c3b are weight-streaming bound.
 """
 import argparse
 import json
@@ -24,6 +26,17 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_MFMA_F16_TFLOPS = 2500.0  # MI355X dense fp16/bf16 MFMA
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (see
+# profiles/), scaled by the factor the same counters read for a plain copy of known size.
+# workload -> kernel -> bytes; None where not measured.
+MEASURED_TRAFFIC = {
+    "c2_llama8b_q": {"arcq_gemm": 57392933, "arcq_quantize_act": 22006181},
+    "c4_qwen32b_mlp": {"arcq_gemm": 783594845, "arcq_quantize_act": 55137233},
+    "c5_llama70b_down": {"arcq_gemm": 1786293815, "arcq_quantize_act": 607603255},
+    "c3a_llama8b_up": {"arcq_gemm": 36080215, "arcq_quantize_act": 352768},
+    "c3b_llama8b_down": {"arcq_gemm": 35072989, "arcq_quantize_act": 1100288},
+}
+
 
 def quantizer_bytes(M, K, S):
     """Algorithmic HBM bytes of one quantizer launch: fp16 row in, codes and scale bytes out
@@ -37,65 +50,87 @@ def gemm_flops(M, N, Kp):
 
 
 def gemm_bytes(M, N, Kp, out_bytes=2):
+    """Algorithmic bytes of one GEMM launch: both packed operands once, the output once."""
     return (M + N) * (Kp // 2 + Kp // 16) + M * N * out_bytes
 
 
-def measure(torch, B, case, steps, warmup):
-    """Runs warmup + steps of (quantize_act, gemm); returns wall ms per step and per-kernel ms."""
+def measure(torch, B, case, steps, warmup, vendor_ref=True):
+    """Runs warmup + steps of (quantize_act, gemm) on the current stream; per-kernel times come
+    from events recorded on that same stream around each launch inside the timed region."""
     import numpy as np
     wl = case["wl"]
     d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     X, W, perm = d(case["X"]), d(case["W"]), d(case["perm"])
     S, sTx, sTw = case["S"], float(case["sT_x"]), float(case["sT_w"])
     wc, wsc = B.arcq_pack_weight(W, perm, S, sTw)          # offline
-    del W
     Kp = wl.K + S
     ac = torch.empty((wl.M, Kp // 2), dtype=torch.uint8, device="cuda")
     asc = torch.empty((wl.M, Kp // 16), dtype=torch.uint8, device="cuda")
     Y = torch.empty((wl.M, wl.N), dtype=torch.float16, device="cuda")
     need = B.arcq_gemm_workspace_size(wl.M, wl.N, Kp)
     ws = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda")
-
-    def step(ev=None):
-        if ev:
-            ev[0].record()
-        B.arcq_quantize_act(X, perm, S, sTx, codes=ac, scales=asc)
-        if ev:
-            ev[1].record()
-        B.arcq_gemm(ac, asc, sTx, wc, wsc, sTw, y=Y, workspace=ws)
-        if ev:
-            ev[2].record()
+    quant = B.prepare_quantize_act(X, perm, S, sTx, ac, asc)
+    gemm = B.prepare_gemm(ac, asc, sTx, wc, wsc, sTw, Y, ws)
 
     for _ in range(warmup):
-        step()
+        quant()
+        gemm()
     torch.cuda.synchronize()
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     t0 = time.perf_counter()
-    for i in range(steps):
-        step(evs[i])
+    for e in evs:
+        e[0].record()
+        quant()
+        e[1].record()
+        gemm()
+        e[2].record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-    q_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / steps
-    g_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / steps
-    # device-side time of the whole step sequence (first event to last event)
-    dev_ms = evs[0][0].elapsed_time(evs[-1][2]) / steps
-    return {"wall_ms": wall_ms, "dev_ms": dev_ms, "quant_ms": q_ms, "gemm_ms": g_ms}
+    out = {
+        "wall_ms": wall_ms,
+        "dev_ms": evs[0][0].elapsed_time(evs[-1][2]) / steps,     # first event to last event
+        "quant_ms": sum(e[0].elapsed_time(e[1]) for e in evs) / steps,
+        "gemm_ms": sum(e[1].elapsed_time(e[2]) for e in evs) / steps,
+    }
+    if vendor_ref:
+        # context only: the vendor library's bf16 GEMM (hipBLASLt through torch.matmul) on the
+        # unquantized operands, K columns (no augmentation); not part of the product path
+        Xb, Wb = X.to(torch.bfloat16), W.to(torch.bfloat16)
+        for _ in range(3):
+            Xb @ Wb.t()
+        torch.cuda.synchronize()
+        n = max(3, min(steps, 20))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            Xb @ Wb.t()
+        e1.record()
+        torch.cuda.synchronize()
+        out["vendor_bf16_gemm_ms"] = e0.elapsed_time(e1) / n
+    return out
 
 
 def summarize(wl, S, t):
     Kp = wl.K + S
     fl = gemm_flops(wl.M, wl.N, Kp)
     qb = quantizer_bytes(wl.M, wl.K, S)
-    return {
+    gb = gemm_bytes(wl.M, wl.N, Kp)
+    s = {
         "M": wl.M, "K": wl.K, "N": wl.N, "S": S,
         "step_ms": round(t["dev_ms"], 5), "quant_ms": round(t["quant_ms"], 5), "gemm_ms": round(t["gemm_ms"], 5),
         "step_tflops": round(fl / t["dev_ms"] / 1e9, 2),
         "gemm_tflops": round(fl / t["gemm_ms"] / 1e9, 2),
         "gemm_frac_of_f16_mfma_peak": round(fl / t["gemm_ms"] / 1e9 / PEAK_MFMA_F16_TFLOPS, 4),
-        "gemm_weight_stream_gbs": round(gemm_bytes(wl.M, wl.N, Kp) / t["gemm_ms"] / 1e6, 1),
+        "gemm_operand_gbs": round(gb / t["gemm_ms"] / 1e6, 1),
+        "gemm_frac_of_hbm_peak": round(gb / t["gemm_ms"] / 1e6 / PEAK_HBM_GBS, 4),
         "quant_gbs": round(qb / t["quant_ms"] / 1e6, 1),
         "quant_frac_of_hbm_peak": round(qb / t["quant_ms"] / 1e6 / PEAK_HBM_GBS, 4),
     }
+    if "vendor_bf16_gemm_ms" in t:
+        s["vendor_bf16_gemm_ms"] = round(t["vendor_bf16_gemm_ms"], 5)
+        s["linear_vs_vendor_bf16"] = round(t["vendor_bf16_gemm_ms"] / t["dev_ms"], 3)   # > 1: quantized linear is faster
+    s["traffic_bytes"] = MEASURED_TRAFFIC.get(wl.name)
+    return s
 
 
 def cpu_baseline(case):
@@ -138,6 +173,10 @@ def main():
     ap.add_argument("--also", default="c4_qwen32b_mlp,c5_llama70b_down,c3a_llama8b_up,c3b_llama8b_down",
                     help="comma-separated extra workloads reported under 'also' (fewer steps); '' for none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-vendor-ref", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run three plain 1 GiB device copies (a kernel of known traffic, for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc pass)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; rows of X shard across GPUs with no exchange, "
@@ -154,37 +193,48 @@ def main():
     B.lib()                                              # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
     wl = wk.WORKLOADS[args.workload]
     case = wk.make_case(wl)
-    t = measure(torch, B, case, args.steps, args.warmup)
+    t = measure(torch, B, case, args.steps, args.warmup, not args.no_vendor_ref)
     s = summarize(wl, case["S"], t)
     Kp = wl.K + case["S"]
-    fl = gemm_flops(wl.M, wl.N, Kp)
 
     also = {}
     for name in [n for n in args.also.split(",") if n and n != args.workload]:
         w2 = wk.WORKLOADS[name]
         c2 = wk.make_case(w2)
         n_steps = 5 if w2.M * w2.N * w2.K > 1e12 else 20
-        also[name] = summarize(w2, c2["S"], measure(torch, B, c2, n_steps, 2))
+        also[name] = summarize(w2, c2["S"], measure(torch, B, c2, n_steps, 2, not args.no_vendor_ref))
         del c2
         torch.cuda.empty_cache()
 
+    traffic = MEASURED_TRAFFIC.get(args.workload, {})
     out = {
-        "metric": "augmented NVFP4 GEMM TFLOPS (2*M*N*K') over quantizer+GEMM step; quantizer GB/s and % of MI355X roofline alongside",
+        "metric": "augmented NVFP4 GEMM TFLOPS (2*M*N*K') over the quantizer+GEMM step; quantizer GB/s and % of MI355X roofline alongside",
         "value": s["step_tflops"], "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(t["wall_ms"], 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16", "dtype_note": "NVFP4 (E2M1 x E4M3) operands decoded exactly to f16 for the MFMA, f32 accumulate; quantizer arithmetic in f32",
+        "vs_baseline": None, "dtype": "f16",
+        "dtype_note": "NVFP4 (E2M1 x E4M3) operands decoded exactly to f16 for the MFMA, f32 accumulate; quantizer arithmetic in f32",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: X fp16 [{wl.M},{wl.K}] -> W4A4 linear N={wl.N}, S={case['S']}, K'={Kp}",
                    "outliers": f"{wl.n_outlier} channels {wl.outlier}", "seed": wl.seed},
         "roofline": {"kernel": "arcq_gemm", "bound": "mfma", "achieved": s["gemm_tflops"], "peak": PEAK_MFMA_F16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(s["gemm_tflops"] / PEAK_MFMA_F16_TFLOPS, 4), "traffic": None},
+                     "unit": "TFLOP/s", "frac": round(s["gemm_tflops"] / PEAK_MFMA_F16_TFLOPS, 4),
+                     "traffic": traffic.get("arcq_gemm")},
         "roofline_quantizer": {"kernel": "arcq_quantize_act", "bound": "hbm", "achieved": s["quant_gbs"],
                                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": s["quant_frac_of_hbm_peak"],
-                               "traffic": None,
-                               "note": "this workload (22 MB) is cache-resident: effective GB/s; see also.c5 for HBM streaming"},
+                               "traffic": traffic.get("arcq_quantize_act"),
+                               "note": "this workload (22 MB) is cache-resident: effective GB/s; the HBM-streaming figure is also.c5_llama70b_down.quant_gbs"},
         "detail": s, "also": also,
     }
     if not args.no_cpu_baseline:

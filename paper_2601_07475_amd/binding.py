@@ -135,6 +135,36 @@ def arcq_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_sca
     return y
 
 
+def prepare_quantize_act(x, perm, S, tensor_scale, codes, scales):
+    """Marshals the arguments of arcq_quantize_act once; returns a zero-argument callable that
+    enqueues the call on the stream that was current at preparation time (for tight loops)."""
+    rows, K = x.shape
+    fn = lib().arcq_quantize_act
+    args = (_ptr(x), rows, K, x.stride(0) if rows > 1 else K, _ptr(perm), S, float(tensor_scale),
+            _ptr(codes), _ptr(scales), _stream())
+
+    def call():
+        _check(fn(*args))
+    return call
+
+
+def prepare_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, y, workspace=None):
+    """Same for arcq_gemm."""
+    M, N, Kp = a_codes.shape[0], w_codes.shape[0], a_codes.shape[1] * 2
+    need = arcq_gemm_workspace_size(M, N, Kp)
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    if need > ws_bytes:
+        raise ArcqError(WORKSPACE_TOO_SMALL, f"workspace of {need} bytes needed")
+    fn = lib().arcq_gemm
+    args = (_ptr(a_codes), _ptr(a_scales), float(a_tensor_scale), _ptr(w_codes), _ptr(w_scales),
+            float(w_tensor_scale), M, N, Kp, _ptr(y), DTYPE_F16 if y.dtype == torch.float16 else DTYPE_F32,
+            y.stride(0) if M > 1 else N, _ptr(workspace) if workspace is not None else None, ws_bytes, _stream())
+
+    def call():
+        _check(fn(*args))
+    return call
+
+
 def arcq_check_perm(perm):
     """True if the int32 cuda tensor perm is a permutation of 0..K-1 (synchronises)."""
     K = perm.numel()
