@@ -212,8 +212,8 @@ def main():
     for name in [n for n in args.also.split(",") if n and n != args.workload]:
         w2 = wk.WORKLOADS[name]
         c2 = wk.make_case(w2)
-        n_steps = 5 if w2.M * w2.N * w2.K > 1e12 else 20
-        also[name] = summarize(w2, c2["S"], measure(torch, B, c2, n_steps, 2, not args.no_vendor_ref))
+        n_steps = 10 if w2.M * w2.N * w2.K > 1e12 else 20
+        also[name] = summarize(w2, c2["S"], measure(torch, B, c2, n_steps, 4, not args.no_vendor_ref))
         del c2
         torch.cuda.empty_cache()
 

@@ -108,6 +108,44 @@ __device__ __forceinline__ void store_tile(const float16v (&acc)[WM][WN], int m0
         }
 }
 
+// The same tile computed with the operands swapped (weights as the row operand): lane holds
+// output ROW m (lane % 32) and register e holds column 8 * (e / 4) + 4 * (lane / 32) + e % 4, so
+// every group of four registers is four consecutive n of one row of y: one 8-byte (fp16) or
+// 16-byte (fp32) store instead of four scalar ones.  `vec_ok`: y and ldy allow such stores.
+__device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
+    *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+}
+__device__ __forceinline__ void store4(_Float16* p, float a, float b, float c, float d) {
+    typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+    *reinterpret_cast<half4v*>(p) = half4v{(_Float16)a, (_Float16)b, (_Float16)c, (_Float16)d};
+}
+template <int WM, int WN, typename OutT>
+__device__ __forceinline__ void store_tile_swapped(const float16v (&acc)[WM][WN], int m0, int n0, int r, int h, int M,
+                                                   int N, float alpha, OutT* __restrict__ y, int64_t ldy, bool vec_ok) {
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+        const int m = m0 + 32 * i + r;
+        if (m >= M) continue;
+        OutT* yrow = y + (int64_t)m * ldy;
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + 32 * j + 8 * g + 4 * h;
+                const float v0 = acc[i][j][4 * g] * alpha, v1 = acc[i][j][4 * g + 1] * alpha,
+                            v2 = acc[i][j][4 * g + 2] * alpha, v3 = acc[i][j][4 * g + 3] * alpha;
+                if (vec_ok && n + 3 < N) {
+                    store4(yrow + n, v0, v1, v2, v3);
+                } else {
+                    if (n < N) store_out(yrow + n, v0);
+                    if (n + 1 < N) store_out(yrow + n + 1, v1);
+                    if (n + 2 < N) store_out(yrow + n + 2, v2);
+                    if (n + 3 < N) store_out(yrow + n + 3, v3);
+                }
+            }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Fallback: any K' (multiple of 16), operands read straight from global memory.
 // Workgroup = 4 waves (2 x 2), tile 128 x 128, each wave 64 x 64.
@@ -220,7 +258,9 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(
     const uint32_t adj_c0 = lp_ * 16u, adj_c1 = (lp_ & 1u) * 16u, adj_s = (uint32_t)(tid & 1) * 4u;
     const int crow = tid >> 2, srow = tid >> 1; // row of this thread inside a 64-row / 128-row copy
     const uint32_t cpitch32 = (uint32_t)nbk * 8u, spitch32 = (uint32_t)nbk;
-    const uint32_t wave_slot = (uint32_t)(tid & ~63);   // lane l of a DMA writes slot wave_slot + l
+    // lane l of a DMA writes slot wave_slot + l; made a scalar once so that the LDS destinations
+    // of all copies are computed on the scalar unit
+    const uint32_t wave_slot = __builtin_amdgcn_readfirstlane((uint32_t)(tid & ~63));
     const uint32_t lds0 = lds_address(lds);
     // DMA instruction d (0 .. NDMA-1) of a stage: A code pieces, W code pieces, A scales, W scales.
     auto issue_one = [&](int d, int stage, int buf) {
@@ -347,7 +387,8 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(
 #pragma unroll
                 for (int q = 2 * p; q < 2 * p + 2; ++q) {
                     const int i = q / WN, j = q % WN;
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[x & 1][i], fw[x & 1][j], acc[i][j], 0, 0, 0);
+                    // weights as the row operand: see store_tile_swapped
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[x & 1][j], fa[x & 1][i], acc[i][j], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (FULL && x < 6) {            // copies of stage s+2, spread over steps 0..5
@@ -374,7 +415,8 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(
     wait_vmcnt<0>();                            // no copy may still be in flight when the LDS is released
 
     const int m0 = wg_m0 + wrow0, n0 = wg_n0 + wcol0;
-    store_tile<WM, WN>(acc, m0, n0, r, h, M, N, alpha, y, ldy);
+    const bool vec_ok = (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
+    store_tile_swapped<WM, WN>(acc, m0, n0, r, h, M, N, alpha, y, ldy, vec_ok);
 }
 
 template <int WM, int WN, typename OutT>
