@@ -185,8 +185,12 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Staged kernel for K' % 64 == 0.  Workgroup = 4 waves (2 x 2); each wave owns WM x WN MFMA
-// tiles of 32 x 32, so the workgroup tile is BM x BN = 64 WM x 64 WN.
+// Staged kernel for K' % 64 == 0.  Workgroup = GM x GN waves; each wave owns WM x WN MFMA tiles
+// of 32 x 32, so the workgroup tile is BM x BN = 32 WM GM x 32 WN GN.  With 4 waves (one per
+// SIMD, up to 256 accumulator registers) the hand-made schedule has to hide every stall.  8 waves
+// (two per SIMD, 128 accumulator registers each, <2,4,4,2> / <4,2,2,4>) let the hardware interleave
+// two waves but decode every fragment for more waves; they measured 4 % slower on the large
+// shapes (the kernel is limited by power, not by issue slots), so 2 x 2 waves are dispatched.
 //
 // A stage is 128 k (8 blocks): per row 64 bytes of codes and 8 scale bytes, kept PACKED in
 // LDS (4.5 bits per element) and decoded in registers after the LDS read.  Stages travel
@@ -200,9 +204,10 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(
 // (row >> 1) & 3 so that the 16-byte reads of 8 consecutive rows fall in 8 different bank groups.
 // A wave-wide DMA instruction writes lane l to (uniform base) + 16 l, so the swizzle is applied
 // by choosing which global piece each lane fetches.
-template <int WM, int WN>
+template <int WM, int WN, int GM, int GN>
 struct StagedCfg {
-    static constexpr int BM = 64 * WM, BN = 64 * WN;
+    static constexpr int BM = 32 * WM * GM, BN = 32 * WN * GN;
+    static constexpr int NT = 64 * GM * GN;              // threads
     static constexpr int A_CODES = 0;
     static constexpr int W_CODES = BM * 64;
     static constexpr int A_SCALES = (BM + BN) * 64;
@@ -211,15 +216,17 @@ struct StagedCfg {
     static constexpr int NSTAGE = 3;
     static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
     // DMA instructions per thread per stage: 16-byte pieces of codes, 4-byte pieces of scales
-    static constexpr int NDMA = (BM + BN) / 64 + (BM + BN) / 128;
+    static constexpr int NA = BM * 4 / NT, NW = BN * 4 / NT, NAS = BM * 2 / NT, NWS = BN * 2 / NT;
+    static constexpr int NDMA = NA + NW + NAS + NWS;
+    static_assert(NA * NT == BM * 4 && NW * NT == BN * 4 && NAS * NT == BM * 2 && NWS * NT == BN * 2, "tile / thread mismatch");
 };
 
-template <int WM, int WN, typename OutT>
-__global__ __launch_bounds__(256) void gemm_staged_kernel(
+template <int WM, int WN, int GM, int GN, typename OutT>
+__global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N,
     int nbk, float alpha, OutT* __restrict__ y, int64_t ldy, int tiles_m, int tiles_n) {
-    using C = StagedCfg<WM, WN>;
+    using C = StagedCfg<WM, WN, GM, GN>;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     // ---- workgroup -> tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its
@@ -242,8 +249,8 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(
     const int wave = tid >> 6;
     const int r = lane & 31, h = lane >> 5;
     const int wg_m0 = tile_m * C::BM, wg_n0 = tile_n * C::BN;
-    const int wrow0 = (wave >> 1) * (32 * WM);       // first row of this wave inside the A tile
-    const int wcol0 = (wave & 1) * (32 * WN);        // first row of this wave inside the W tile
+    const int wrow0 = (wave / GN) * (32 * WM);       // first row of this wave inside the A tile
+    const int wcol0 = (wave % GN) * (32 * WN);       // first row of this wave inside the W tile
 
     // ---- DMA source offsets of this thread (bytes from the operand base)
     // When K' is an odd multiple of 64 the last stage is half a stage (4 blocks): the lanes that
@@ -253,10 +260,10 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(
     const int nstage = (nbk >> 3) + (has_half ? 1 : 0);
     // Offsets are recomputed per copy (a handful of ALU operations per stage) rather than kept
     // in registers: the accumulators leave this kernel 256 registers and it needs most of them.
-    // (s & 3) and the row swizzle repeat every 256 slots, so one value serves every copy
+    // (s & 3) and the row swizzle repeat every 64 slots, so one value serves every copy
     const uint32_t lp_ = (uint32_t)((tid & 3) ^ ((tid >> 3) & 3));
     const uint32_t adj_c0 = lp_ * 16u, adj_c1 = (lp_ & 1u) * 16u, adj_s = (uint32_t)(tid & 1) * 4u;
-    const int crow = tid >> 2, srow = tid >> 1; // row of this thread inside a 64-row / 128-row copy
+    const int crow = tid >> 2, srow = tid >> 1; // row of this thread inside a copy of NT/4 code rows / NT/2 scale rows
     const uint32_t cpitch32 = (uint32_t)nbk * 8u, spitch32 = (uint32_t)nbk;
     // lane l of a DMA writes slot wave_slot + l; made a scalar once so that the LDS destinations
     // of all copies are computed on the scalar unit
@@ -268,23 +275,23 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(
         const bool half = has_half && stage == nstage - 1;
         const uint32_t oc = (uint32_t)stage * 64u + (half ? adj_c1 : adj_c0);
         const uint32_t os = (uint32_t)stage * 8u + (half ? 0u : adj_s);
-        constexpr int NA = C::BM / 64, NW = C::BN / 64, NAS = C::BM / 128;
+        constexpr int NA = C::NA, NW = C::NW, NAS = C::NAS, NT = C::NT;
         // rows past the edge of the operand re-read its last row (never stored)
         if (d < NA) {
-            const uint32_t row = (uint32_t)min(wg_m0 + d * 64 + crow, M - 1);
-            dma16(a_codes, row * cpitch32 + oc, base + C::A_CODES + 16u * (d * 256 + wave_slot));
+            const uint32_t row = (uint32_t)min(wg_m0 + d * (NT / 4) + crow, M - 1);
+            dma16(a_codes, row * cpitch32 + oc, base + C::A_CODES + 16u * (d * NT + wave_slot));
         } else if (d < NA + NW) {
             const int p = d - NA;
-            const uint32_t row = (uint32_t)min(wg_n0 + p * 64 + crow, N - 1);
-            dma16(w_codes, row * cpitch32 + oc, base + C::W_CODES + 16u * (p * 256 + wave_slot));
+            const uint32_t row = (uint32_t)min(wg_n0 + p * (NT / 4) + crow, N - 1);
+            dma16(w_codes, row * cpitch32 + oc, base + C::W_CODES + 16u * (p * NT + wave_slot));
         } else if (d < NA + NW + NAS) {
             const int p = d - NA - NW;
-            const uint32_t row = (uint32_t)min(wg_m0 + p * 128 + srow, M - 1);
-            dma4(a_scales, row * spitch32 + os, base + C::A_SCALES + 4u * (p * 256 + wave_slot));
+            const uint32_t row = (uint32_t)min(wg_m0 + p * (NT / 2) + srow, M - 1);
+            dma4(a_scales, row * spitch32 + os, base + C::A_SCALES + 4u * (p * NT + wave_slot));
         } else {
             const int p = d - NA - NW - NAS;
-            const uint32_t row = (uint32_t)min(wg_n0 + p * 128 + srow, N - 1);
-            dma4(w_scales, row * spitch32 + os, base + C::W_SCALES + 4u * (p * 256 + wave_slot));
+            const uint32_t row = (uint32_t)min(wg_n0 + p * (NT / 2) + srow, N - 1);
+            dma4(w_scales, row * spitch32 + os, base + C::W_SCALES + 4u * (p * NT + wave_slot));
         }
     };
     auto issue_all = [&](int stage, int buf) {
@@ -419,17 +426,17 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(
     store_tile_swapped<WM, WN>(acc, m0, n0, r, h, M, N, alpha, y, ldy, vec_ok);
 }
 
-template <int WM, int WN, typename OutT>
+template <int WM, int WN, int GM, int GN, typename OutT>
 arcq_status launch_staged(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                           const uint8_t* w_scales, int M, int N, int nbk, float alpha, OutT* y, int64_t ldy,
                           hipStream_t stream) {
-    using C = StagedCfg<WM, WN>;
-    auto kern = gemm_staged_kernel<WM, WN, OutT>;
+    using C = StagedCfg<WM, WN, GM, GN>;
+    auto kern = gemm_staged_kernel<WM, WN, GM, GN, OutT>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
     const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), C::LDS_BYTES, stream, a_codes, a_scales, w_codes,
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales, w_codes,
                        w_scales, M, N, nbk, alpha, y, ldy, tiles_m, tiles_n);
     return check_launch("gemm_staged_kernel");
 }
@@ -561,11 +568,11 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
         // big tiles when they still give every CU work; otherwise smaller ones
         const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
         if (t256 >= 256)
-            return launch_staged<4, 4>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+            return launch_staged<4, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
         const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
         if (t128x256 >= 192)
-            return launch_staged<2, 4>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
-        return launch_staged<2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+            return launch_staged<2, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+        return launch_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
     }
     dim3 grid((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128));
     hipLaunchKernelGGL(gemm_direct_kernel<OutT>, grid, dim3(256), 0, stream, a_codes, a_scales, w_codes, w_scales,
