@@ -135,6 +135,37 @@ def quantize_act(X, perm, S, s_T):
     return pack_nibbles(codes.reshape(M, Kp)), sb.reshape(M, Kp // G)
 
 
+def rmsnorm(X, gamma, eps):
+    """RMSNorm in front of the quantizer (Section 3.3 lists it as part of the fused kernel; the
+    paper gives no formula, so this is the standard definition y = x / sqrt(mean(x^2) + eps) * gamma
+    with the arithmetic of the reference Llama/Qwen layer, every rounding listed):
+
+      ms   = fl32( (sum_i x_i^2) / K )      sum and division in float64 (each x_i^2 is exact)
+      rstd = fl32( 1 / fl32( sqrt( fl32(ms + eps) ) ) )        IEEE fp32 add, sqrt, divide
+      t_i  = fl16( fl32(x_i * rstd) )                           normalised value in the model dtype
+      y_i  = fl16( t_i * gamma_i )                              product of two fp16, rounded once
+
+    X fp16 [M, K], gamma fp16 [K], eps float; returns fp16 [M, K].
+    """
+    X = np.asarray(X)
+    gamma = np.asarray(gamma)
+    assert X.dtype == np.float16 and gamma.dtype == np.float16 and gamma.shape == (X.shape[1],)
+    eps = _f32(eps)
+    if not (np.isfinite(eps) and eps >= 0):
+        raise ValueError("eps must be finite and >= 0")
+    x64 = X.astype(np.float64)
+    ms = ((x64 * x64).sum(axis=1) / X.shape[1]).astype(np.float32)
+    rstd = _f32(1.0) / np.sqrt((ms + eps).astype(np.float32)).astype(np.float32)
+    t = (X.astype(np.float32) * rstd[:, None]).astype(np.float32).astype(np.float16)
+    # fp16 x fp16 is exact in fp32 (22 significant bits); one rounding to fp16
+    return (t.astype(np.float32) * gamma.astype(np.float32)[None, :]).astype(np.float16)
+
+
+def rmsnorm_quantize_act(X, gamma, eps, perm, S, s_T):
+    """The fused kernel of Section 3.3: RMSNorm, then the online activation quantizer."""
+    return quantize_act(rmsnorm(X, gamma, eps), perm, S, s_T)
+
+
 def pack_weight(W, perm, S, s_T):
     """Offline weight packer (Section 3.2 "Offline Weight Quantization").
 

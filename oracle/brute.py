@@ -65,6 +65,62 @@ def round_f32(q):
     return -r if q < 0 else r
 
 
+def round_f16(q):
+    """Nearest IEEE binary16 value (ties to even) of a rational, as a Fraction (no overflow handling)."""
+    q = Fr(q)
+    if q == 0:
+        return q
+    a = abs(q)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fr(2) ** e > a:
+        e -= 1
+    e = max(e, -14)
+    quantum = Fr(2) ** (e - 10)
+    r = round(a / quantum) * quantum
+    return -r if q < 0 else r
+
+
+def sqrt_f32(v):
+    """Correctly rounded binary32 square root of a positive fp32-valued rational, decided exactly:
+    lo = largest fp32 value <= sqrt(v); the upper neighbour is taken iff (lo + ulp/2)^2 <= v (a tie
+    cannot occur: the square of a midpoint has too many bits to be an fp32 value)."""
+    v = Fr(v)
+    assert v > 0
+    from math import isqrt
+    shift = 400                                          # guard bits: floor(sqrt(v)) to 2^-200
+    root = Fr(isqrt(int(v * Fr(2) ** shift)), 2 ** (shift // 2))
+    lo = round_f32_down(root)
+    e = lo.numerator.bit_length() - lo.denominator.bit_length()
+    if Fr(2) ** e > lo:
+        e -= 1
+    ulp = Fr(2) ** (max(e, -126) - 23)
+    mid = lo + ulp / 2
+    return lo + ulp if mid * mid <= v else lo
+
+
+def round_f32_down(q):
+    """Largest binary32 value <= q (q > 0)."""
+    q = Fr(q)
+    e = q.numerator.bit_length() - q.denominator.bit_length()
+    if Fr(2) ** e > q:
+        e -= 1
+    quantum = Fr(2) ** (max(e, -126) - 23)
+    return (q // quantum) * quantum
+
+
+def rmsnorm_row(x, gamma, eps):
+    """One row of the RMSNorm recipe of oracle.arcquant.rmsnorm in exact rationals with hand-made
+    roundings.  x, gamma: fp16-valued numbers; eps fp32-valued.  Returns a list of Fractions."""
+    x = [Fr(v) for v in x]
+    ms = round_f32(sum(v * v for v in x) / len(x))       # the float64 sum is exact for these tests' inputs
+    rstd = round_f32(1 / sqrt_f32(round_f32(ms + Fr(eps))))
+    out = []
+    for v, g in zip(x, gamma):
+        t = round_f16(round_f32(v * rstd))
+        out.append(round_f16(t * Fr(g)))
+    return out
+
+
 def quantize_block(v, s_T):
     """v: 16 numbers exactly representable in fp32 (floats or Fractions), s_T fp32-valued.
     Returns (scale_byte, [16 codes], [16 residuals as Fractions]).

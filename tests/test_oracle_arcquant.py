@@ -269,3 +269,72 @@ def test_gemm_against_triple_loop():
 def test_all_workloads_have_valid_shapes():
     for wl in wk.WORKLOADS.values():
         assert wl.K % 16 == 0 and wl.S % 16 == 0 and 0 < wl.S <= wl.K and wl.n_outlier < wl.S
+
+
+# ---- RMSNorm in front of the quantizer (Section 3.3 fused kernel) ---------------------------------
+def _norm_inputs(M=6, K=96, seed=21):
+    rng = np.random.default_rng(seed)
+    X = (rng.standard_normal((M, K)) * rng.uniform(0.05, 30, (M, 1))).astype(np.float16)
+    X[:, 5] *= np.float16(40)
+    gamma = (1 + 0.3 * rng.standard_normal(K)).astype(np.float16)
+    return X, gamma
+
+
+def test_rmsnorm_against_plain_torch_reference():
+    import torch
+    X, gamma = _norm_inputs(M=64, K=512)
+    eps = 1e-5
+    y = A.rmsnorm(X, gamma, eps)
+    # the usual reference layer, written with library primitives (fp32 statistics, cast, then weight)
+    xt = torch.from_numpy(X)
+    var = xt.float().pow(2).mean(-1, keepdim=True)
+    ref = (torch.from_numpy(gamma) * (xt.float() * torch.rsqrt(var + eps)).to(torch.float16)).numpy()
+    # fp32 accumulation order and rsqrt rounding may move a value by one fp16 step, rarely
+    same = (y == ref)
+    assert same.mean() > 0.995
+    ulp = np.abs(y.view(np.int16).astype(np.int32) - ref.view(np.int16).astype(np.int32))
+    assert ulp.max() <= 1
+
+
+def test_rmsnorm_closed_forms_and_invariants():
+    K = 64
+    gamma = np.ones(K, np.float16)
+    # constant row: every entry becomes sign(c) (rms = |c|)
+    for c in (0.5, -3.0, 120.0):
+        y = A.rmsnorm(np.full((1, K), c, np.float16), gamma, 0.0)
+        assert np.all(y == np.float16(np.sign(c)))
+    # scaling a row by a power of two changes nothing when eps = 0 (every step scales exactly)
+    X, g2 = _norm_inputs(M=8, K=K)
+    X = (X / 64).astype(np.float16)                      # keep 4x inside the fp16 range, away from subnormals
+    assert np.array_equal(A.rmsnorm(X, g2, 0.0), A.rmsnorm((X * np.float16(4)).astype(np.float16), g2, 0.0))
+    # unit root-mean-square after normalisation (gamma = 1), up to fp16 rounding
+    y = A.rmsnorm(X, gamma, 0.0).astype(np.float64)
+    assert np.allclose(np.sqrt((y * y).mean(axis=1)), 1.0, rtol=2e-3)
+    # gamma enters as a per-channel factor applied after the cast
+    y1 = A.rmsnorm(X, gamma, 1e-6)
+    yg = A.rmsnorm(X, g2, 1e-6)
+    assert np.array_equal(yg, (y1.astype(np.float32) * g2.astype(np.float32)).astype(np.float16))
+    # a large eps shrinks the output; zero row stays zero
+    assert np.all(np.abs(A.rmsnorm(X, gamma, 100.0).astype(np.float32)) <= np.abs(y1.astype(np.float32)))
+    assert np.all(A.rmsnorm(np.zeros((1, K), np.float16), gamma, 1e-6) == 0)
+    with pytest.raises(ValueError):
+        A.rmsnorm(X, gamma, -1.0)
+
+
+def test_rmsnorm_against_exact_rational_brute_force():
+    X, gamma = _norm_inputs(M=5, K=48, seed=22)
+    for eps in (0.0, 1e-6, 1e-5):
+        y = A.rmsnorm(X, gamma, eps)
+        for m in range(X.shape[0]):
+            want = brute.rmsnorm_row([float(v) for v in X[m]], [float(g) for g in gamma], float(np.float32(eps)))
+            assert [float(v) for v in want] == y[m].astype(np.float64).tolist(), (m, eps)
+
+
+def test_fused_rmsnorm_quantizer_is_the_composition():
+    X, gamma = _norm_inputs(M=10, K=128, seed=23)
+    perm = wk.calibrate_perm(A.rmsnorm(X, gamma, 1e-5))
+    sT = wk.tensor_scale(A.rmsnorm(X, gamma, 1e-5))
+    c1, s1 = A.rmsnorm_quantize_act(X, gamma, 1e-5, perm, 32, sT)
+    c2, s2 = A.quantize_act(A.rmsnorm(X, gamma, 1e-5), perm, 32, sT)
+    assert np.array_equal(c1, c2) and np.array_equal(s1, s2)
+    assert c1.shape == (10, 80) and s1.shape == (10, 10)
