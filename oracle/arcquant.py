@@ -140,7 +140,9 @@ def rmsnorm(X, gamma, eps):
     paper gives no formula, so this is the standard definition y = x / sqrt(mean(x^2) + eps) * gamma
     with the arithmetic of the reference Llama/Qwen layer, every rounding listed):
 
-      ms   = fl32( (sum_i x_i^2) / K )      sum and division in float64 (each x_i^2 is exact)
+      ms   = fl32( fl64( fl64(sum_i x_i^2) / K ) )   the sum itself is EXACT (integer arithmetic: every
+                                            fp16 value is a multiple of 2^-24), rounded once to float64,
+                                            divided in float64, rounded to fp32 -- no summation order
       rstd = fl32( 1 / fl32( sqrt( fl32(ms + eps) ) ) )        IEEE fp32 add, sqrt, divide
       t_i  = fl16( fl32(x_i * rstd) )                           normalised value in the model dtype
       y_i  = fl16( t_i * gamma_i )                              product of two fp16, rounded once
@@ -153,8 +155,17 @@ def rmsnorm(X, gamma, eps):
     eps = _f32(eps)
     if not (np.isfinite(eps) and eps >= 0):
         raise ValueError("eps must be finite and >= 0")
-    x64 = X.astype(np.float64)
-    ms = ((x64 * x64).sum(axis=1) / X.shape[1]).astype(np.float32)
+    M, K = X.shape
+    sumsq = np.empty(M, dtype=np.float64)
+    for r0 in range(0, M, 256):                                # chunks only bound the memory of the big integers
+        scaled = X[r0:r0 + 256].astype(np.float64) * 2.0 ** 24
+        v = scaled.astype(np.int64)
+        if not np.array_equal(v, scaled):
+            raise ValueError("non-finite input")
+        v = v.astype(object)
+        n = (v * v).sum(axis=1)                                # Python integers: exact, any order
+        sumsq[r0:r0 + 256] = [float(t) for t in n]             # int -> float64 is correctly rounded
+    ms = (sumsq * 2.0 ** -48 / K).astype(np.float32)
     rstd = _f32(1.0) / np.sqrt((ms + eps).astype(np.float32)).astype(np.float32)
     t = (X.astype(np.float32) * rstd[:, None]).astype(np.float32).astype(np.float16)
     # fp16 x fp16 is exact in fp32 (22 significant bits); one rounding to fp16

@@ -65,6 +65,19 @@ def round_f32(q):
     return -r if q < 0 else r
 
 
+def round_f64(q):
+    """Nearest IEEE binary64 value (ties to even) of a positive rational in the normal range, as a Fraction."""
+    q = Fr(q)
+    if q == 0:
+        return q
+    assert q > 0
+    e = q.numerator.bit_length() - q.denominator.bit_length()
+    if Fr(2) ** e > q:
+        e -= 1
+    quantum = Fr(2) ** (e - 52)
+    return round(q / quantum) * quantum
+
+
 def round_f16(q):
     """Nearest IEEE binary16 value (ties to even) of a rational, as a Fraction (no overflow handling)."""
     q = Fr(q)
@@ -112,7 +125,7 @@ def rmsnorm_row(x, gamma, eps):
     """One row of the RMSNorm recipe of oracle.arcquant.rmsnorm in exact rationals with hand-made
     roundings.  x, gamma: fp16-valued numbers; eps fp32-valued.  Returns a list of Fractions."""
     x = [Fr(v) for v in x]
-    ms = round_f32(sum(v * v for v in x) / len(x))       # the float64 sum is exact for these tests' inputs
+    ms = round_f32(round_f64(round_f64(sum(v * v for v in x)) / len(x)))
     rstd = round_f32(1 / sqrt_f32(round_f32(ms + Fr(eps))))
     out = []
     for v, g in zip(x, gamma):

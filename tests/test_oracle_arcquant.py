@@ -323,6 +323,9 @@ def test_rmsnorm_closed_forms_and_invariants():
 
 def test_rmsnorm_against_exact_rational_brute_force():
     X, gamma = _norm_inputs(M=5, K=48, seed=22)
+    # a row whose squares span 2^-48 .. 2^31: no floating-point order sums it exactly
+    X[4, :] = np.float16(2.0 ** -24)
+    X[4, 0], X[4, 1], X[4, 2] = np.float16(-60000.0), np.float16(0.3333), np.float16(6.1e-5)
     for eps in (0.0, 1e-6, 1e-5):
         y = A.rmsnorm(X, gamma, eps)
         for m in range(X.shape[0]):
