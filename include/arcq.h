@@ -83,6 +83,22 @@ arcq_status arcq_quantize_act(const void* x, int64_t M, int64_t K, int64_t ldx,
                               uint8_t* codes, uint8_t* scales, void* stream);
 
 /*
+ * The same quantizer with RMSNorm in front, as one kernel (Section 3.3: the fused quantization
+ * kernel integrates channel reordering, RMSNorm, primary and residual quantization).  The paper
+ * gives no formula; this is y = x / sqrt(mean(x^2) + eps) * gamma with the roundings of the
+ * reference layer: mean of squares summed in fp64 and rounded to fp32, rstd = 1/sqrt(ms + eps)
+ * in fp32 (correctly rounded), x * rstd rounded to fp16, times gamma rounded to fp16; the result
+ * equals arcq_quantize_act applied to that fp16 tensor.  tensor_scale refers to the NORMALISED
+ * activations.
+ * gamma  fp16 [K], indexed by SOURCE channel (before the permutation), 16-byte aligned
+ * eps    finite, >= 0
+ */
+arcq_status arcq_rmsnorm_quantize_act(const void* x, int64_t M, int64_t K, int64_t ldx,
+                                      const void* gamma, float eps,
+                                      const int32_t* perm, int64_t S, float tensor_scale,
+                                      uint8_t* codes, uint8_t* scales, void* stream);
+
+/*
  * Offline weight packer (Section 3.2 "Offline Weight Quantization"): reorder the
  * K axis of w with the same perm, quantize every block of 16 (plain
  * round-to-nearest), then append a verbatim copy of the codes and scale bytes of

@@ -23,6 +23,7 @@ SIGNATURES = {
     "arcq_last_error": (ctypes.c_char_p, []),
     "arcq_packed_sizes": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
     "arcq_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _vp, _vp, _vp]),
+    "arcq_rmsnorm_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _i64, _f32, _vp, _vp, _vp]),
     "arcq_pack_weight": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _vp, _vp, _vp]),
     "arcq_gemm_workspace_size": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
     "arcq_gemm": (ctypes.c_int, [_vp, _vp, _f32, _vp, _vp, _f32, _i64, _i64, _i64, _vp, ctypes.c_int, _i64,
@@ -100,6 +101,16 @@ def arcq_quantize_act(x, perm, S, tensor_scale, codes=None, scales=None):
     return _quantize(lib().arcq_quantize_act, x, perm, S, tensor_scale, codes, scales)
 
 
+def arcq_rmsnorm_quantize_act(x, gamma, eps, perm, S, tensor_scale, codes=None, scales=None):
+    """RMSNorm (weight gamma fp16 [K], eps) fused in front of arcq_quantize_act."""
+    assert gamma.is_cuda and gamma.dtype == torch.float16 and gamma.is_contiguous() and gamma.numel() == x.shape[1]
+    lib_fn = lib().arcq_rmsnorm_quantize_act
+
+    def fn(xp, rows, K, ldx, permp, S_, sT, cp, sp, st):
+        return lib_fn(xp, rows, K, ldx, _ptr(gamma), float(eps), permp, S_, sT, cp, sp, st)
+    return _quantize(fn, x, perm, S, tensor_scale, codes, scales)
+
+
 def arcq_pack_weight(w, perm, S, tensor_scale, codes=None, scales=None):
     """w fp16 [N, K] cuda -> packed [N, K'] with the outlier blocks duplicated."""
     return _quantize(lib().arcq_pack_weight, w, perm, S, tensor_scale, codes, scales)
@@ -142,6 +153,18 @@ def prepare_quantize_act(x, perm, S, tensor_scale, codes, scales):
     fn = lib().arcq_quantize_act
     args = (_ptr(x), rows, K, x.stride(0) if rows > 1 else K, _ptr(perm), S, float(tensor_scale),
             _ptr(codes), _ptr(scales), _stream())
+
+    def call():
+        _check(fn(*args))
+    return call
+
+
+def prepare_rmsnorm_quantize_act(x, gamma, eps, perm, S, tensor_scale, codes, scales):
+    """Same for arcq_rmsnorm_quantize_act."""
+    rows, K = x.shape
+    fn = lib().arcq_rmsnorm_quantize_act
+    args = (_ptr(x), rows, K, x.stride(0) if rows > 1 else K, _ptr(gamma), float(eps), _ptr(perm), S,
+            float(tensor_scale), _ptr(codes), _ptr(scales), _stream())
 
     def call():
         _check(fn(*args))

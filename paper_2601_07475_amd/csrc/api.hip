@@ -47,19 +47,22 @@ arcq_status check_KS(int64_t K, int64_t S) {
 
 arcq_status quantize_entry(int mode, const char* who, const void* x, int64_t rows, int64_t K, int64_t ldx,
                            const int32_t* perm, int64_t S, float s_T, uint8_t* codes, uint8_t* scales,
-                           void* stream) {
+                           void* stream, bool norm = false, const void* gamma = nullptr, float eps = 0.0f) {
     clear_error();
     if (arcq_status st = check_KS(K, S)) return st;
     if (rows < 0 || rows > 0x7FFFFFFF) return fail(ARCQ_BAD_SHAPE, "%s: rows = %lld out of range", who, (long long)rows);
     if (ldx < K) return fail(ARCQ_BAD_SHAPE, "%s: leading dimension %lld < K = %lld", who, (long long)ldx, (long long)K);
     if (arcq_status st = check_scale(s_T, "tensor_scale")) return st;
+    if (norm && (!std::isfinite(eps) || eps < 0.0f)) return fail(ARCQ_INVALID_ARG, "%s: eps = %g must be finite and >= 0", who, (double)eps);
     if (rows == 0) return ARCQ_OK;
-    if (!x || !perm || !codes || !scales) return fail(ARCQ_INVALID_ARG, "%s: null pointer", who);
+    if (!x || !perm || !codes || !scales || (norm && !gamma)) return fail(ARCQ_INVALID_ARG, "%s: null pointer", who);
+    if (norm && !aligned(gamma, 16)) return fail(ARCQ_BAD_ALIGN, "%s: gamma must be 16-byte aligned", who);
     if (!aligned(x, 16) || (ldx % 8) != 0)
         return fail(ARCQ_BAD_ALIGN, "%s: input must be 16-byte aligned with a leading dimension that is a multiple of 8", who);
     if (!aligned(codes, 8)) return fail(ARCQ_BAD_ALIGN, "%s: codes must be 8-byte aligned", who);
     if (!aligned(perm, 4)) return fail(ARCQ_BAD_ALIGN, "%s: perm must be 4-byte aligned", who);
-    return launch_quantize(mode, x, rows, K, ldx, perm, S, s_T, codes, scales, static_cast<hipStream_t>(stream));
+    return launch_quantize(mode, x, rows, K, ldx, perm, S, s_T, codes, scales, norm ? gamma : nullptr, eps,
+                           static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -86,6 +89,13 @@ arcq_status arcq_packed_sizes(int64_t rows, int64_t K, int64_t S, size_t* codes_
 arcq_status arcq_quantize_act(const void* x, int64_t M, int64_t K, int64_t ldx, const int32_t* perm, int64_t S,
                               float tensor_scale, uint8_t* codes, uint8_t* scales, void* stream) {
     return quantize_entry(0, "arcq_quantize_act", x, M, K, ldx, perm, S, tensor_scale, codes, scales, stream);
+}
+
+arcq_status arcq_rmsnorm_quantize_act(const void* x, int64_t M, int64_t K, int64_t ldx, const void* gamma, float eps,
+                                      const int32_t* perm, int64_t S, float tensor_scale, uint8_t* codes,
+                                      uint8_t* scales, void* stream) {
+    return quantize_entry(0, "arcq_rmsnorm_quantize_act", x, M, K, ldx, perm, S, tensor_scale, codes, scales, stream,
+                          true, gamma, eps);
 }
 
 arcq_status arcq_pack_weight(const void* w, int64_t N, int64_t K, int64_t ldw, const int32_t* perm, int64_t S,

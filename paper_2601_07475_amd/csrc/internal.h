@@ -16,9 +16,10 @@ void clear_error();
 arcq_status check_launch(const char* what);
 
 // mode 0: activations (residual blocks appended); mode 1: weights (outlier blocks duplicated).
+// gamma != nullptr (mode 0 only): RMSNorm with that weight and eps in front of the quantizer.
 arcq_status launch_quantize(int mode, const void* x, int64_t rows, int64_t K, int64_t ldx,
                             const int32_t* perm, int64_t S, float s_T,
-                            uint8_t* codes, uint8_t* scales, hipStream_t stream);
+                            uint8_t* codes, uint8_t* scales, const void* gamma, float eps, hipStream_t stream);
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t Kp);
 arcq_status launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales,

@@ -64,4 +64,36 @@ __device__ __forceinline__ void wg_barrier() {
     asm volatile("" ::: "memory");
 }
 
+// Small LDS accesses issued through inline assembly, for bookkeeping words that live beside a
+// buffer with copies in flight: the compiler does not see them as LDS accesses, so it does not
+// wait for those copies first.  The caller orders them with wait_lgkmcnt0() and wg_barrier().
+__device__ __forceinline__ void lds_add_u64(uint32_t addr, uint64_t v) {
+    asm volatile("ds_add_u64 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_add_f64(uint32_t addr, double v) {
+    asm volatile("ds_add_f64 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_write_u64(uint32_t addr, uint64_t v) {
+    asm volatile("ds_write_b64 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_write_f32(uint32_t addr, float v) {
+    asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+// The two reads wait for their own result (and every older LDS operation of the wave).
+__device__ __forceinline__ uint64_t lds_read_u64(uint32_t addr) {
+    uint64_t v;
+    asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+__device__ __forceinline__ double lds_read_f64(uint32_t addr) {
+    double v;
+    asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+__device__ __forceinline__ float lds_read_f32(uint32_t addr) {
+    float v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+
 }  // namespace arcq

@@ -83,6 +83,17 @@ def weights(wl, chunk_rows=2048):
     return W
 
 
+def rmsnorm_gamma(wl):
+    """RMSNorm weight fp16 [K] for the fused norm + quantizer: near 1 with a 10 % spread, and the
+    few channels of trained models that carry a much larger or much smaller weight."""
+    rng = np.random.default_rng([wl.seed, 14])
+    g = 1.0 + 0.1 * rng.standard_normal(wl.K)
+    n_odd = max(1, wl.K // 128)
+    odd = rng.choice(wl.K, size=n_odd, replace=False)
+    g[odd] *= rng.choice([0.05, 0.25, 4.0, 12.0], size=n_odd)
+    return g.astype(np.float16)
+
+
 def calibrate_perm(X):
     """Calibration stand-in: perm[j] = source channel placed at reordered position j,
     channels in ascending order of abs-max, ties by lower channel index first, so the

@@ -86,6 +86,96 @@ def test_quantize_act_bit_exact(M, K, S):
     assert_same_bytes(got_c, want_c, "codes")
 
 
+def norm_case(M, K, S, seed):
+    """Pre-norm hidden states, RMSNorm weight, and a permutation / tensor scale calibrated on the
+    normalised activations (the quantizer's input)."""
+    wl = wk.Workload("t", M, K, 8, S, max(1, K // 100), "loguniform20_100", 0.02, seed)
+    X = wk.activations(wl)
+    gamma = wk.rmsnorm_gamma(wl)
+    Yn = A.rmsnorm(X, gamma, 1e-5)
+    return X, gamma, wk.calibrate_perm(Yn), wk.tensor_scale(Yn)
+
+
+def gpu_norm_quantize(X, gamma, eps, perm, S, sT):
+    g = dev(gamma)
+
+    def fn(x, p, S_, t, codes, scales):
+        return B.arcq_rmsnorm_quantize_act(x, g, eps, p, S_, t, codes=codes, scales=scales)
+    return gpu_quantize(fn, X, perm, S, sT)
+
+
+NORM_SHAPES = [  # blocks per lane 1..4, one and two row buffers, lane tails, S = 0 and S = K
+    (1, 16, 0), (5, 48, 48), (16, 512, 32), (33, 1040, 1040), (67, 4096, 256), (300, 5120, 512),
+    (9, 8192, 0), (5, 14336, 256), (4, 16400, 4800), (3, 28672, 1024), (2, 40000, 16), (2, 65536, 2048),
+]
+
+
+@pytest.fixture(params=["bracketed_sum", "integer_sum"])
+def stats_path(request, monkeypatch):
+    """The kernel sums the squares in fp64 and falls back to an exact integer sum for the rare row
+    whose mean it cannot round with certainty; the environment switch sends every row through the
+    integer sum, so both paths are held to the same oracle."""
+    if request.param == "integer_sum":
+        monkeypatch.setenv("ARCQ_RMSNORM_EXACT_SUM", "1")
+    else:
+        monkeypatch.delenv("ARCQ_RMSNORM_EXACT_SUM", raising=False)
+    return request.param
+
+
+@pytest.mark.parametrize("M,K,S", NORM_SHAPES)
+def test_rmsnorm_quantize_act_bit_exact(M, K, S, stats_path):
+    say(f"rmsnorm_quantize_act parity M={M} K={K} S={S} {stats_path}")
+    X, gamma, perm, sT = norm_case(M, K, S, seed=300 + K % 89)
+    for eps in (1e-5, 0.0):
+        want_c, want_s = A.rmsnorm_quantize_act(X, gamma, eps, perm, S, sT)
+        got_c, got_s = gpu_norm_quantize(X, gamma, eps, perm, S, sT)
+        assert_same_bytes(got_s, want_s, f"scales eps={eps}")
+        assert_same_bytes(got_c, want_c, f"codes eps={eps}")
+
+
+def test_rmsnorm_quantize_edge_rows_and_strided_input(stats_path):
+    """Rows that stress the statistics: all zero (eps decides), one huge value among subnormals
+    (squares from 2^-48 to 2^31), constant rows, a row of fp16 maxima, rows whose mean square is an
+    exact fp32 midpoint (the kernel's fp64 bracket cannot decide those); input with ldx > K."""
+    say(f"rmsnorm_quantize_act edge rows {stats_path}")
+    K, S = 1024, 64
+    rng = np.random.default_rng(77)
+    X = (rng.standard_normal((12, K)) * 2).astype(np.float16)
+    X[0] = 0
+    X[1] = np.float16(2.0 ** -24)
+    X[1, 5], X[1, 700] = np.float16(-60000.0), np.float16(0.3333)
+    X[2] = np.float16(-3.0)
+    X[3] = np.float16(65504.0)
+    X[4] = (rng.standard_normal(K) * 2.0 ** -20).astype(np.float16)      # subnormal inputs only
+    X[5, ::2] = 0
+    X[6] = 0
+    X[6, 3], X[6, 900] = np.float16(32.0), np.float16(2.0 ** -7)         # mean square 1 + 2^-24: tie, rounds to even
+    X[7] = 0
+    X[7, 1000], X[7, 2], X[7, 77] = np.float16(-32.0), np.float16(2.0 ** -7), np.float16(2.0 ** -6.5)  # close to a midpoint
+    assert ((X[6].astype(np.float64) ** 2).sum() / K) == 1.0 + 2.0 ** -24
+    gamma = wk.rmsnorm_gamma(wk.Workload("t", 12, K, 8, S, 8, "const50", 0.02, 78))
+    gamma[3] = np.float16(0.0)
+    for eps in (1e-6, 1e-2):
+        Yn = A.rmsnorm(X, gamma, eps)
+        perm, sT = wk.calibrate_perm(Yn), wk.tensor_scale(Yn)
+        want_c, want_s = A.quantize_act(Yn, perm, S, sT)
+        wide = torch.full((12, K + 40), 3.0, dtype=torch.float16, device="cuda")
+        wide[:, :K] = dev(X)
+        cc, ss = B.arcq_rmsnorm_quantize_act(wide[:, :K], dev(gamma), eps, dev(perm), S, sT)
+        assert_same_bytes(ss.cpu().numpy(), want_s, f"scales eps={eps}")
+        assert_same_bytes(cc.cpu().numpy(), want_c, f"codes eps={eps}")
+
+
+def test_rmsnorm_quantize_full_size_qproj(stats_path):
+    """The layer input RMSNorm feeds in practice, at full size: 2048 tokens x 4096 hidden, S = 256."""
+    say(f"rmsnorm_quantize_act full size 2048 x 4096 {stats_path}")
+    X, gamma, perm, sT = norm_case(2048, 4096, 256, seed=41)
+    want_c, want_s = A.rmsnorm_quantize_act(X, gamma, 1e-5, perm, 256, sT)
+    got_c, got_s = gpu_norm_quantize(X, gamma, 1e-5, perm, 256, sT)
+    assert_same_bytes(got_s, want_s, "scales")
+    assert_same_bytes(got_c, want_c, "codes")
+
+
 @pytest.mark.parametrize("N,K,S", [(1, 16, 16), (40, 512, 32), (300, 4096, 256), (17, 14336, 256), (5, 28672, 1024)])
 def test_pack_weight_bit_exact(N, K, S):
     say(f"pack_weight parity N={N} K={K} S={S}")

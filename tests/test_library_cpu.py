@@ -69,6 +69,26 @@ def test_quantizer_argument_errors(fn):
     assert B.lib().arcq_last_error() == b""
 
 
+def qn(x=FAKE, rows=4, K=512, ld=512, gamma=FAKE, eps=1e-5, perm=FAKE, S=32, sT=1.0, codes=FAKE, scales=FAKE):
+    return B.lib().arcq_rmsnorm_quantize_act(x, rows, K, ld, gamma, eps, perm, S, sT, codes, scales, None)
+
+
+def test_rmsnorm_quantizer_argument_errors():
+    assert qn(K=500) == B.BAD_SHAPE
+    assert qn(S=24) == B.BAD_SHAPE
+    assert qn(ld=496) == B.BAD_SHAPE
+    assert qn(sT=0.0) == B.INVALID_ARG
+    for bad in (-1e-6, float("inf"), float("nan")):
+        assert qn(eps=bad) == B.INVALID_ARG
+    assert b"eps" in B.lib().arcq_last_error()
+    assert qn(gamma=None) == B.INVALID_ARG
+    assert qn(x=None) == B.INVALID_ARG
+    assert qn(gamma=ctypes.c_void_p(0x10008)) == B.BAD_ALIGN
+    assert qn(x=ODD) == B.BAD_ALIGN
+    assert qn(codes=ODD) == B.BAD_ALIGN
+    assert qn(rows=0, x=None, gamma=None, perm=None, codes=None, scales=None) == B.OK
+
+
 def g(ac=FAKE, asc=FAKE, sa=1.0, wc=FAKE, wsc=FAKE, sw=1.0, M=4, N=8, Kp=64, y=FAKE, dt=0, ldy=8, ws=None, wsb=0):
     return B.lib().arcq_gemm(ac, asc, sa, wc, wsc, sw, M, N, Kp, y, dt, ldy, ws, wsb, None)
 
