@@ -90,6 +90,12 @@ __device__ __forceinline__ double lds_read_f64(uint32_t addr) {
     asm volatile("ds_read_b64 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
     return v;
 }
+typedef uint32_t lds_u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ lds_u32x4_t lds_read_b128(uint32_t addr) {       // addr 16-byte aligned
+    lds_u32x4_t v;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
 __device__ __forceinline__ float lds_read_f32(uint32_t addr) {
     float v;
     asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");

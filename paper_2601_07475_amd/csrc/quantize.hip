@@ -73,7 +73,8 @@ __device__ __forceinline__ double row16_sum(double v) {
 }
 
 template <int BPT, int MODE, bool DB, bool STREAM, int NORM>
-__global__ __launch_bounds__(1024) void quantize_rows_kernel(
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(BPT == 1 ? (NORM ? 6 : 8) : 4)))
+void quantize_rows_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int rows, int K, int S,
     const int32_t* __restrict__ perm, float s_T, float ginv,
     uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
@@ -176,19 +177,21 @@ __global__ __launch_bounds__(1024) void quantize_rows_kernel(
             // rounding is monotone.  If the two agree, that is the answer.
             // Otherwise (a row whose mean sits within delta of an fp32 rounding boundary, a few in 10^5)
             // the workgroup redoes the sum in integer arithmetic below.
-            // Every channel of the row is gathered by exactly one lane (perm is a permutation), so the
-            // lanes' own gathered values cover the row.
             if (!force_exact) {
+                // each lane sums the contiguous 16-byte pieces it copied itself: wide, conflict-free reads
                 double part = 0.0;
 #pragma unroll
-                for (int j = 0; j < BPT; ++j) {
-                    double p = 0.0;
+                for (int p = 0; p < NPRE; ++p) {
+                    const lds_u32x4_t q4 = lds_read_b128(lds_address(lds_row) + base + 16u * (uint32_t)(tid + p * T));
+                    double s8 = 0.0;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float f = __half2float(*reinterpret_cast<const __half*>(lds_row + base + off[j][i]));
-                        p += (double)(f * f);
+                    for (int e = 0; e < 4; ++e) {
+                        const float lo = __half2float(__ushort_as_half((unsigned short)(q4[e] & 0xFFFFu)));
+                        const float hi = __half2float(__ushort_as_half((unsigned short)(q4[e] >> 16)));
+                        s8 += (double)(lo * lo);
+                        s8 += (double)(hi * hi);
                     }
-                    part += tid + j * T < nb ? p : 0.0;                 // duplicate lanes count nothing
+                    part += tid + p * T < n16 ? s8 : 0.0;               // slots past the row hold a duplicate
                 }
                 part = row16_sum(part);
                 if ((tid & 15) == 0) lds_add_f64(acc, part);
@@ -210,7 +213,8 @@ __global__ __launch_bounds__(1024) void quantize_rows_kernel(
             if (tid == 0) lds_write_u64(acc ^ 8u, 0);
             acc ^= 8u;
             if (__builtin_amdgcn_readfirstlane(decided ? 1 : 0) == 0) {     // the same in every wave of the workgroup
-                // Exact path.  x * 2^24 is an integer below 2^40; split as a * 2^20 + b with a, b < 2^20:
+                // Exact path.  Every channel of the row is gathered by exactly one lane (perm is a
+                // permutation), so the lanes' own gathered values cover the row.  x * 2^24 is an integer below 2^40; split as a * 2^20 + b with a, b < 2^20:
                 //   (x 2^24)^2 = a^2 2^40 + 2 a b 2^20 + b^2.
                 // The three sums stay integers below 2^53 in fp64 up to a row of 16 lanes (64 terms per lane
                 // at most, each below 2^40), and go on as 64-bit integers from there (below 2^56 for K <= 65536).
@@ -281,17 +285,21 @@ __global__ __launch_bounds__(1024) void quantize_rows_kernel(
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const __half h = *reinterpret_cast<const __half*>(lds_row + base + off[j][i]);
-                v[i] = __half2float(h);
                 if (NORM) {
-                    // The product is pinned to a register between the multiply and the conversion: fused
-                    // into one mixed-precision multiply-add the compiler adds +0, which turns -0 into +0.
-                    float prod = v[i] * rstd;
+                    // t = fl16(fl32(x * rstd)): two roundings, as the reference layer does it.  The product is
+                    // pinned to a register between them; left alone the compiler fuses multiply and conversion
+                    // into one mixed-precision multiply-add, which rounds once (a different fp16 value once in
+                    // some 10^7 elements) and adds +0 (so -0 becomes +0).
+                    float prod = __half2float(h) * rstd;
                     asm volatile("" : "+v"(prod));
-                    const __half t = __float2half_rn(prod);                      // normalised, model dtype
+                    const __half t16 = __float2half_rn(prod);
                     const __half g = GAMMA_REGS
                         ? __ushort_as_half((unsigned short)((gam[j][i >> 1] >> (16 * (i & 1))) & 0xFFFFu))
                         : *reinterpret_cast<const __half*>(lds_gamma + off[j][i]);
-                    v[i] = __half2float(__float2half_rn(__half2float(t) * __half2float(g)));   // exact product, one rounding
+                    // fp16 times fp16 rounded once to fp16
+                    v[i] = __half2float(__hmul(t16, g));
+                } else {
+                    v[i] = __half2float(h);
                 }
             }
             uint32_t sbyte, lo, hi;
