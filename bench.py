@@ -7,6 +7,10 @@ K' = K + S.  Weights are packed once, offline, outside the timed region (Section
 Weight Quantization").  The default workload is the LLaMA-3-8B q_proj prefill shape
 (M=2048, K=4096, N=4096, S=256).
 
+The timed region holds exactly --steps steps and nothing else on the stream; the same steps are
+then repeated with an event after every launch, which gives the per-kernel launch durations the
+rooflines use (those events cost a few microseconds per step, so they stay out of the timed region).
+
 Prints ONE JSON line.  `value` = 2*M*N*K' / step time, in TFLOP/s.  `roofline` prices the dominant
 kernel (the GEMM; fp16 MFMA peak because operands are decoded exactly to fp16).  `cpu_baseline`
 is the numpy oracle timed on the host cores on the same workload.  `also` holds the other
@@ -30,11 +34,11 @@ PEAK_MFMA_F16_TFLOPS = 2500.0  # MI355X dense fp16/bf16 MFMA
 # profiles/), scaled by the factor the same counters read for a plain copy of known size.
 # workload -> kernel -> bytes; None where not measured.
 MEASURED_TRAFFIC = {
-    "c2_llama8b_q": {"arcq_gemm": 57392933, "arcq_quantize_act": 22006181},
-    "c4_qwen32b_mlp": {"arcq_gemm": 783594845, "arcq_quantize_act": 55137233},
-    "c5_llama70b_down": {"arcq_gemm": 1786293815, "arcq_quantize_act": 607603255},
-    "c3a_llama8b_up": {"arcq_gemm": 36080215, "arcq_quantize_act": 352768},
-    "c3b_llama8b_down": {"arcq_gemm": 35072989, "arcq_quantize_act": 1100288},
+    "c2_llama8b_q": {"arcq_gemm": 57307136, "arcq_quantize_act": 22005760, "arcq_rmsnorm_quantize_act": 22118400},
+    "c4_qwen32b_mlp": {"arcq_gemm": 779497472, "arcq_quantize_act": 55145472, "arcq_rmsnorm_quantize_act": 55264256},
+    "c5_llama70b_down": {"arcq_gemm": 1843289088, "arcq_quantize_act": 621447168, "arcq_rmsnorm_quantize_act": 636225536},
+    "c3a_llama8b_up": {"arcq_gemm": 36067328, "arcq_quantize_act": 350208, "arcq_rmsnorm_quantize_act": 464896},
+    "c3b_llama8b_down": {"arcq_gemm": 35061760, "arcq_quantize_act": 1097728, "arcq_rmsnorm_quantize_act": 1376256},
 }
 
 
@@ -76,8 +80,20 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
         quant()
         gemm()
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    # timed region: exactly `steps` steps, nothing but the two launches per step on the stream
+    first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    first.record()
+    for _ in range(steps):
+        quant()
+        gemm()
+    last.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    dev_ms = first.elapsed_time(last) / steps
+    # the same steps again with an event after every launch: per-kernel launch durations for the
+    # rooflines (the extra events cost a few microseconds per step, so they stay out of the region above)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     for e in evs:
         e[0].record()
         quant()
@@ -85,13 +101,28 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
         gemm()
         e[2].record()
     torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     out = {
         "wall_ms": wall_ms,
-        "dev_ms": evs[0][0].elapsed_time(evs[-1][2]) / steps,     # first event to last event
+        "dev_ms": dev_ms,
         "quant_ms": sum(e[0].elapsed_time(e[1]) for e in evs) / steps,
         "gemm_ms": sum(e[1].elapsed_time(e[2]) for e in evs) / steps,
     }
+    # the quantizer with RMSNorm fused in front (Section 3.3), on the same tensor taken as the
+    # pre-norm hidden state: its own figure, not part of the step
+    from paper_2601_07475_amd import workloads as wk
+    gamma = d(wk.rmsnorm_gamma(wl))
+    nq = B.prepare_rmsnorm_quantize_act(X, gamma, 1e-5, perm, S, sTx, ac, asc)
+    for _ in range(3):
+        nq()
+    torch.cuda.synchronize()
+    n = max(3, min(steps, 20))
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for e0, e1 in pairs:
+        e0.record()
+        nq()
+        e1.record()
+    torch.cuda.synchronize()
+    out["rmsnorm_quant_ms"] = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / n
     if vendor_ref:
         # context only: the vendor library's bf16 GEMM (hipBLASLt through torch.matmul) on the
         # unquantized operands, K columns (no augmentation); not part of the product path
@@ -125,6 +156,8 @@ def summarize(wl, S, t):
         "gemm_frac_of_hbm_peak": round(gb / t["gemm_ms"] / 1e6 / PEAK_HBM_GBS, 4),
         "quant_gbs": round(qb / t["quant_ms"] / 1e6, 1),
         "quant_frac_of_hbm_peak": round(qb / t["quant_ms"] / 1e6 / PEAK_HBM_GBS, 4),
+        "rmsnorm_quant_ms": round(t["rmsnorm_quant_ms"], 5),
+        "rmsnorm_quant_gbs": round((qb + 2 * wl.K) / t["rmsnorm_quant_ms"] / 1e6, 1),
     }
     if "vendor_bf16_gemm_ms" in t:
         s["vendor_bf16_gemm_ms"] = round(t["vendor_bf16_gemm_ms"], 5)

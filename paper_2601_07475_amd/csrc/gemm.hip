@@ -189,15 +189,17 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(
 // of 32 x 32, so the workgroup tile is BM x BN = 32 WM GM x 32 WN GN.  With 4 waves (one per
 // SIMD, up to 256 accumulator registers) the hand-made schedule has to hide every stall.  8 waves
 // (two per SIMD, 128 accumulator registers each, <2,4,4,2> / <4,2,2,4>) let the hardware interleave
-// two waves but decode every fragment for more waves; they measured 4 % slower on the large
-// shapes (the kernel is limited by power, not by issue slots), so 2 x 2 waves are dispatched.
+// two waves but decode every fragment for more waves; on the large shapes they measure the same as
+// 2 x 2 waves to within 1 % (the loop is limited by the vector and matrix work itself, not by
+// stalls: removing the waits or the barrier from a timing build gains 2 %), so 2 x 2 waves are
+// dispatched there; on a 128 x 256 tile, 2 x 4 waves of 64 x 64 are 5 % faster than 2 x 2 of 64 x 128.
 //
 // A stage is 128 k (8 blocks): per row 64 bytes of codes and 8 scale bytes, kept PACKED in
 // LDS (4.5 bits per element) and decoded in registers after the LDS read.  Stages travel
-// global -> LDS with global_load_lds (no register staging) through a ring of 3 buffers: the
-// loads of stage s+2 are issued right after the barrier that opens stage s, so they have two
-// stage times to land, and one barrier per stage suffices (passing the barrier of stage s
-// means every wave has finished stage s-1, whose buffer stage s+2 reuses).
+// global -> LDS with global_load_lds (no register staging) through a ring of NSTAGE (3 to 5)
+// buffers: the loads of stage s + NSTAGE - 1 are issued right after the barrier that opens stage s,
+// so they have NSTAGE - 1 stage times to land, and one barrier per stage suffices (passing the
+// barrier of stage s means every wave has finished stage s-1, whose buffer the new stage reuses).
 //
 // LDS layout of one stage (bytes):  A codes [BM][64] | W codes [BN][64] | A scales [BM][8] |
 // W scales [BN][8].  The four 16-byte pieces of a row's codes are stored XOR-swizzled with
@@ -208,17 +210,22 @@ template <int WM, int WN, int GM, int GN>
 struct StagedCfg {
     static constexpr int BM = 32 * WM * GM, BN = 32 * WN * GN;
     static constexpr int NT = 64 * GM * GN;              // threads
-    static constexpr int A_CODES = 0;
-    static constexpr int W_CODES = BM * 64;
-    static constexpr int A_SCALES = (BM + BN) * 64;
-    static constexpr int W_SCALES = A_SCALES + BM * 8;
-    static constexpr int STAGE_BYTES = (BM + BN) * 72;
-    static constexpr int NSTAGE = 3;
-    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
-    // DMA instructions per thread per stage: 16-byte pieces of codes, 4-byte pieces of scales
-    static constexpr int NA = BM * 4 / NT, NW = BN * 4 / NT, NAS = BM * 2 / NT, NWS = BN * 2 / NT;
+    // DMA instructions per thread per stage: 16-byte pieces of codes, 4-byte pieces of scales.  A copy
+    // always involves the whole workgroup; when an operand has fewer pieces than threads the surplus
+    // lanes re-fetch its last rows into padding behind the region (so every wave issues the same
+    // number of copies, which the counted waits rely on).
+    static constexpr int NA = (BM * 4 + NT - 1) / NT, NW = (BN * 4 + NT - 1) / NT;
+    static constexpr int NAS = (BM * 2 + NT - 1) / NT, NWS = (BN * 2 + NT - 1) / NT;
     static constexpr int NDMA = NA + NW + NAS + NWS;
-    static_assert(NA * NT == BM * 4 && NW * NT == BN * 4 && NAS * NT == BM * 2 && NWS * NT == BN * 2, "tile / thread mismatch");
+    static constexpr int A_CODES = 0;
+    static constexpr int W_CODES = NA * NT * 16;
+    static constexpr int A_SCALES = W_CODES + NW * NT * 16;
+    static constexpr int W_SCALES = A_SCALES + NAS * NT * 4;
+    static constexpr int STAGE_BYTES = W_SCALES + NWS * NT * 4;
+    // Ring depth: a stage is fetched NSTAGE - 1 stages before it is computed (3 measured as good as 5).
+    static constexpr int NSTAGE = 3;
+    static constexpr int DIST = NSTAGE - 1;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
 };
 
 template <int WM, int WN, int GM, int GN, typename OutT>
@@ -323,7 +330,7 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     // compiler from regrouping them, so the matrix pipe stays busy while the vector ALU decodes.
     // The pipeline runs ACROSS stages: the barrier that opens stage s+1 sits before step 6 of
     // stage s; step 6 reads the first raw codes of stage s+1 from LDS and step 7 decodes its
-    // first fragments.  The copies for stage s+2 are issued two per k-step during steps 0-5 of
+    // first fragments.  The copies for stage s + NSTAGE - 1 are issued two per k-step during steps 0-5 of
     // stage s (its buffer was last read in stage s-1, which every wave left before the barrier
     // that opened stage s), so no wave ever queues a burst of memory instructions.
     constexpr int G = WM + WN;                 // fragments per k-step
@@ -365,20 +372,21 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     // past the end of K' it keeps issuing copies (of the last stage, into a free ring slot) and
     // keeps reading and decoding a "next" stage whose values are never used.
     int buf = 0;                                // ring slot of the stage being computed
-    auto ring_next = [](int b) { return b == 2 ? 0 : b + 1; };
+    auto ring_next = [](int b) { return b == C::NSTAGE - 1 ? 0 : b + 1; };
     auto run_stage = [&](int s, auto nsteps_tag) {
         constexpr int NSTEPS = decltype(nsteps_tag)::value;
         constexpr bool FULL = NSTEPS == 8;      // a half stage is always the last one
         const uint8_t* st = lds + buf * C::STAGE_BYTES;
-        const int buf1 = ring_next(buf), buf2 = ring_next(buf1);
-        const int fetch = min(s + 2, nstage - 1);
+        // the copies issued during this stage go to the slot of the stage computed before this one
+        const int buf1 = ring_next(buf), buf2 = buf == 0 ? C::NSTAGE - 1 : buf - 1;
+        const int fetch = min(s + C::DIST, nstage - 1);
 #pragma unroll
         for (int x = 0; x < NSTEPS; ++x) {
             if (x == 0 && FULL) read_raw(1, st);
             if (x == 6) {
-                // stage s+1 must have landed: everything but the NDMA copies issued during steps
-                // 0-5 (younger) has retired once at most NDMA operations are outstanding
-                wait_vmcnt<C::NDMA>();
+                // stage s+1 must have landed: the copies of the DIST - 1 later stages are younger, and
+                // everything older has retired once at most that many operations are outstanding
+                wait_vmcnt<(C::DIST - 1) * C::NDMA>();
                 wg_barrier();
                 read_raw(0, lds + buf1 * C::STAGE_BYTES);
             }
@@ -398,7 +406,7 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[x & 1][j], fa[x & 1][i], acc[i][j], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (FULL && x < 6) {            // copies of stage s+2, spread over steps 0..5
+                if (FULL && x < 6) {            // copies of stage s + NSTAGE - 1, spread over steps 0..5
 #pragma unroll
                     for (int d = 0; d < C::NDMA; ++d)
                         if ((d * 6) / C::NDMA == x && (d - (x * C::NDMA + 5) / 6) == p) issue_one(d, fetch, buf2);
@@ -409,9 +417,9 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
         buf = buf1;
     };
 
-    issue_all(0, 0);
-    issue_all(min(1, nstage - 1), 1);
-    wait_vmcnt<C::NDMA>();
+#pragma unroll
+    for (int d = 0; d < C::DIST; ++d) issue_all(min(d, nstage - 1), d);
+    wait_vmcnt<(C::DIST - 1) * C::NDMA>();
     wg_barrier();
     read_raw(0, lds);
 #pragma unroll
@@ -570,8 +578,10 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
         if (t256 >= 256)
             return launch_staged<4, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
         const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
+        // 128 x 256 tiles with 8 waves of 64 x 64 (two per SIMD): 5 % faster than 4 waves of 64 x 128 on the
+        // 2048 x 4096 x 4352 problem; on the large shapes 4 and 8 waves measure the same
         if (t128x256 >= 192)
-            return launch_staged<2, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+            return launch_staged<2, 2, 2, 4>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
         return launch_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
     }
     dim3 grid((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128));

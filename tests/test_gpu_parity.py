@@ -259,6 +259,8 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     (1, 1, 16, 0), (16, 512, 512, 32), (77, 200, 48, 16), (130, 129, 96, 16), (128, 256, 256, 0),
     (257, 131, 1040, 48), (16, 1000, 4096, 256), (300, 77, 2048, 2048),
     (7, 45, 160, 32), (16, 4097, 1008, 16), (3, 16, 14336, 256), (17, 40, 512, 0), (128, 384, 192, 0), (500, 260, 4160, 64),
+    # ragged edges in every tile configuration of the staged kernel: 128 x 256 tiles (8 waves), 256 x 256 tiles
+    (1990, 4070, 256, 64), (4000, 4100, 128, 64),
 ]
 
 
