@@ -17,6 +17,7 @@
 
 #include <hip/hip_fp16.h>
 
+#include <algorithm>
 #include <type_traits>
 
 namespace arcq {
@@ -232,15 +233,20 @@ template <int WM, int WN, int GM, int GN, typename OutT>
 __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N,
-    int nbk, float alpha, OutT* __restrict__ y, int64_t ldy, int tiles_m, int tiles_n) {
+    int nbk, float alpha, OutT* __restrict__ y, int64_t ldy, int tiles_m, int tiles_n, int splits,
+    int64_t split_stride) {
     using C = StagedCfg<WM, WN, GM, GN>;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     // ---- workgroup -> tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its
     // own L2); give every XCD a contiguous run of the tile sequence, and walk the sequence in
     // column-major groups of 8 tile rows so that concurrently running tiles share A and W rows.
+    // With splits > 1 the reduction dimension is cut into `splits` runs of whole stages: workgroup
+    // blockIdx.x = split * num_tiles + tile accumulates its run and stores an fp32 partial tile at
+    // y + split * split_stride (a reduction kernel adds the partial results).
     const int num_tiles = tiles_m * tiles_n;
-    int pid = blockIdx.x;
+    const int split = (int)blockIdx.x / num_tiles;
+    int pid = (int)blockIdx.x - split * num_tiles;
     if ((num_tiles & 7) == 0) pid = (pid & 7) * (num_tiles >> 3) + (pid >> 3);
     constexpr int GROUP = 8;
     const int group_size = GROUP * tiles_n;
@@ -264,7 +270,10 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     // would fetch its missing second half re-fetch the first half instead (never used), which
     // keeps every access inside the operand.  `half` selects those adjusted offsets.
     const bool has_half = (nbk & 7) != 0;
-    const int nstage = (nbk >> 3) + (has_half ? 1 : 0);
+    const int nstage = (nbk >> 3) + (has_half ? 1 : 0);        // of the whole reduction dimension
+    const int per_split = nstage / splits, extra = nstage % splits;
+    const int s_begin = split * per_split + min(split, extra);  // this workgroup's stages [s_begin, s_end)
+    const int s_end = s_begin + per_split + (split < extra ? 1 : 0);
     // Offsets are recomputed per copy (a handful of ALU operations per stage) rather than kept
     // in registers: the accumulators leave this kernel 256 registers and it needs most of them.
     // (s & 3) and the row swizzle repeat every 64 slots, so one value serves every copy
@@ -379,7 +388,7 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
         const uint8_t* st = lds + buf * C::STAGE_BYTES;
         // the copies issued during this stage go to the slot of the stage computed before this one
         const int buf1 = ring_next(buf), buf2 = buf == 0 ? C::NSTAGE - 1 : buf - 1;
-        const int fetch = min(s + C::DIST, nstage - 1);
+        const int fetch = min(s + C::DIST, s_end - 1);
 #pragma unroll
         for (int x = 0; x < NSTEPS; ++x) {
             if (x == 0 && FULL) read_raw(1, st);
@@ -418,40 +427,81 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     };
 
 #pragma unroll
-    for (int d = 0; d < C::DIST; ++d) issue_all(min(d, nstage - 1), d);
+    for (int d = 0; d < C::DIST; ++d) issue_all(min(s_begin + d, s_end - 1), d);
     wait_vmcnt<(C::DIST - 1) * C::NDMA>();
     wg_barrier();
     read_raw(0, lds);
 #pragma unroll
     for (int gidx = 0; gidx < G; ++gidx) decode_frag(gidx, 0);
     const int nfull = nbk >> 3;
-    for (int s = 0; s < nfull; ++s) run_stage(s, std::integral_constant<int, 8>{});
-    if (has_half) run_stage(nfull, std::integral_constant<int, 4>{});
+    for (int s = s_begin; s < min(s_end, nfull); ++s) run_stage(s, std::integral_constant<int, 8>{});
+    if (has_half && s_end == nstage) run_stage(nfull, std::integral_constant<int, 4>{});
     wait_vmcnt<0>();                            // no copy may still be in flight when the LDS is released
 
     const int m0 = wg_m0 + wrow0, n0 = wg_n0 + wcol0;
     const bool vec_ok = (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
-    store_tile_swapped<WM, WN>(acc, m0, n0, r, h, M, N, alpha, y, ldy, vec_ok);
+    store_tile_swapped<WM, WN>(acc, m0, n0, r, h, M, N, alpha, y + (int64_t)split * split_stride, ldy, vec_ok);
+}
+
+// y = alpha * (sum of the `splits` fp32 partial results [M, N], added in index order).
+template <typename OutT>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int splits,
+                                                            int64_t split_stride, int M, int N, float alpha,
+                                                            OutT* __restrict__ y, int64_t ldy, int vec4) {
+    const int64_t total = vec4 ? (int64_t)M * (N >> 2) : (int64_t)M * N;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        if (vec4) {
+            const int64_t m = idx / (N >> 2), n = 4 * (idx % (N >> 2));
+            float4 sum = *reinterpret_cast<const float4*>(part + m * N + n);
+            for (int sp = 1; sp < splits; ++sp) {
+                const float4 v = *reinterpret_cast<const float4*>(part + sp * split_stride + m * N + n);
+                sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+            }
+            store4(y + m * ldy + n, sum.x * alpha, sum.y * alpha, sum.z * alpha, sum.w * alpha);
+        } else {
+            const int64_t m = idx / N, n = idx % N;
+            float sum = part[m * N + n];
+            for (int sp = 1; sp < splits; ++sp) sum += part[sp * split_stride + m * N + n];
+            store_out(y + m * ldy + n, sum * alpha);
+        }
+    }
 }
 
 template <int WM, int WN, int GM, int GN, typename OutT>
 arcq_status launch_staged(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                           const uint8_t* w_scales, int M, int N, int nbk, float alpha, OutT* y, int64_t ldy,
-                          hipStream_t stream) {
+                          hipStream_t stream, int splits = 1, float* partial = nullptr) {
     using C = StagedCfg<WM, WN, GM, GN>;
+    const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
+    if (splits > 1) {
+        // fp32 partial results [splits, M, N] in the workspace, then one pass that adds them
+        auto kern = gemm_staged_kernel<WM, WN, GM, GN, float>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
+        const int64_t stride = (int64_t)M * N;
+        hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales,
+                           w_codes, w_scales, M, N, nbk, 1.0f, partial, (int64_t)N, tiles_m, tiles_n, splits, stride);
+        if (arcq_status st = check_launch("gemm_staged_kernel (split K)")) return st;
+        const int vec4 = (N & 3) == 0 && (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
+        const int64_t work = vec4 ? stride / 4 : stride;
+        const int blocks = (int)std::min<int64_t>((work + 255) / 256, 4096);
+        hipLaunchKernelGGL(splitk_reduce_kernel<OutT>, dim3(blocks), dim3(256), 0, stream, partial, splits, stride, M, N,
+                           alpha, y, ldy, vec4);
+        return check_launch("splitk_reduce_kernel");
+    }
     auto kern = gemm_staged_kernel<WM, WN, GM, GN, OutT>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
-    const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales, w_codes,
-                       w_scales, M, N, nbk, alpha, y, ldy, tiles_m, tiles_n);
+                       w_scales, M, N, nbk, alpha, y, ldy, tiles_m, tiles_n, 1, (int64_t)0);
     return check_launch("gemm_staged_kernel");
 }
 
 // ---------------------------------------------------------------------------------------------
-// Skinny kernel for M <= 16 (decode): bound by streaming the packed weights once from HBM
-// (9/16 byte per weight), so the layout of the work follows the weight rows.
+// Skinny kernel for M <= 128 (decode, batched decode, short prefill): bound by streaming the packed
+// weights once from HBM (9/16 byte per weight), so the layout of the work follows the weight rows.
 //
 // v_mfma_f32_16x16x32_f16: lane (i = lane % 16, q = lane / 16) supplies 8 consecutive k of row i;
 // the four lane groups q supply different octets.  The activations are the 16-row operand, the
@@ -469,105 +519,160 @@ arcq_status launch_staged(const uint8_t* a_codes, const uint8_t* a_scales, const
 // w*U .. w*U+U-1, then strides on) and add their partial tiles through LDS at the end.
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-template <int NT, int WAVES, int U, typename OutT>
+// MT tiles of 16 activation rows (M <= 16 MT) share every weight fragment a wave loads and decodes:
+// batched decode and short prefills (M up to 128) stay on the weight-streaming path.
+template <int MT, int NT, int WAVES, int U, typename OutT>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N,
     int nbk, float alpha, OutT* __restrict__ y, int64_t ldy) {
-    __shared__ float red[WAVES][NT][4][64];
+    __shared__ float red[WAVES][MT * NT][4][64];
+    static_assert(sizeof(float) * WAVES * MT * NT * 256 <= 64 * 1024, "partial tiles must fit the static LDS limit");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, q = lane >> 4;
     const int n0 = blockIdx.x * (16 * NT);
     const int64_t cpitch = (int64_t)nbk * 8, spitch = nbk;
     const int nchunk = (nbk + 7) >> 3;                       // chunks of 8 blocks, the last may be partial
 
-    const uint8_t* ac = a_codes + (int64_t)min(i, M - 1) * cpitch + 16 * q;
-    const uint8_t* as = a_scales + (int64_t)min(i, M - 1) * spitch + 2 * q;
+    const uint8_t *ac[MT], *as[MT];
+#pragma unroll
+    for (int r = 0; r < MT; ++r) {
+        const int m = min(16 * r + i, M - 1);
+        ac[r] = a_codes + (int64_t)m * cpitch;
+        as[r] = a_scales + (int64_t)m * spitch;
+    }
     const uint8_t *wc[NT], *ws[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int n = min(n0 + 16 * t + i, N - 1);
-        wc[t] = w_codes + n * cpitch + 16 * q;
-        ws[t] = w_scales + n * spitch + 2 * q;
+        wc[t] = w_codes + n * cpitch;
+        ws[t] = w_scales + n * spitch;
     }
-    float4v acc[NT];
+    float4v acc[MT][NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = float4v{0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < MT; ++r)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[r][t] = float4v{0.f, 0.f, 0.f, 0.f};
 
     for (int c0 = wave * U; c0 < nchunk; c0 += WAVES * U) {
-        uint4 ca[U], cw[U][NT];
-        uint32_t sa[U], sw[U][NT];
+        uint4 ca[U][MT], cw[U][NT];
+        uint32_t sa[U][MT], sw[U][NT];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u;
-            // the lane's two blocks exist (nbk is even); otherwise they contribute zero
+            // the lane's two blocks 8c + 2q, 8c + 2q + 1 exist (nbk is even) or lie past the end of the
+            // row: then the lane reads the start of its row instead and both operands count as zero
+            // (codes and scale bytes, so that no stray scale pattern meets a zero)
             const bool ok = 8 * c + 2 * q < nbk;
-            const int cc = ok ? c : 0;
-            ca[u] = *reinterpret_cast<const uint4*>(ac + 64 * (int64_t)cc);
-            sa[u] = *reinterpret_cast<const uint16_t*>(as + 8 * (int64_t)cc);
+            const int64_t co = ok ? 64 * (int64_t)c + 16 * q : 0, so = ok ? 8 * (int64_t)c + 2 * q : 0;
+#pragma unroll
+            for (int r = 0; r < MT; ++r) {
+                ca[u][r] = *reinterpret_cast<const uint4*>(ac[r] + co);
+                sa[u][r] = *reinterpret_cast<const uint16_t*>(as[r] + so);
+                if (!ok) { ca[u][r] = make_uint4(0, 0, 0, 0); sa[u][r] = 0; }
+            }
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                cw[u][t] = *reinterpret_cast<const uint4*>(wc[t] + 64 * (int64_t)cc);
-                sw[u][t] = *reinterpret_cast<const uint16_t*>(ws[t] + 8 * (int64_t)cc);
+                cw[u][t] = *reinterpret_cast<const uint4*>(wc[t] + co);
+                sw[u][t] = *reinterpret_cast<const uint16_t*>(ws[t] + so);
+                if (!ok) { cw[u][t] = make_uint4(0, 0, 0, 0); sw[u][t] = 0; }
             }
-            if (!ok) ca[u] = make_uint4(0, 0, 0, 0);        // zero activations are enough
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const uint32_t a32 = k == 0 ? ca[u].x : k == 1 ? ca[u].y : k == 2 ? ca[u].z : ca[u].w;
-                const half8 fa = decode8(a32, scale_pair(k < 2 ? (sa[u] & 0xFFu) : (sa[u] >> 8)));
+                half8 fa[MT];
+#pragma unroll
+                for (int r = 0; r < MT; ++r) {
+                    const uint32_t a32 = k == 0 ? ca[u][r].x : k == 1 ? ca[u][r].y : k == 2 ? ca[u][r].z : ca[u][r].w;
+                    fa[r] = decode8(a32, scale_pair(k < 2 ? (sa[u][r] & 0xFFu) : (sa[u][r] >> 8)));
+                }
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
                     const uint32_t w32 = k == 0 ? cw[u][t].x : k == 1 ? cw[u][t].y : k == 2 ? cw[u][t].z : cw[u][t].w;
                     const half8 fw = decode8(w32, scale_pair(k < 2 ? (sw[u][t] & 0xFFu) : (sw[u][t] >> 8)));
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa, fw, acc[t], 0, 0, 0);
+#pragma unroll
+                    for (int r = 0; r < MT; ++r)
+                        acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[r], fw, acc[r][t], 0, 0, 0);
                 }
             }
     }
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int r = 0; r < MT; ++r)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) red[wave][t][e][lane] = acc[t][e];
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) red[wave][r * NT + t][e][lane] = acc[r][t][e];
     __syncthreads();
-    for (int idx = threadIdx.x; idx < NT * 4 * 64; idx += WAVES * 64) {
-        const int t = idx >> 8, e = (idx >> 6) & 3, l = idx & 63;
+    for (int idx = threadIdx.x; idx < MT * NT * 4 * 64; idx += WAVES * 64) {
+        const int rt = idx >> 8, e = (idx >> 6) & 3, l = idx & 63;
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) sum += red[w][t][e][l];
-        const int m = 4 * (l >> 4) + e, n = n0 + 16 * t + (l & 15);
+        for (int w = 0; w < WAVES; ++w) sum += red[w][rt][e][l];
+        const int m = 16 * (rt / NT) + 4 * (l >> 4) + e, n = n0 + 16 * (rt % NT) + (l & 15);
         if (m < M && n < N) store_out(y + (int64_t)m * ldy + n, sum * alpha);
     }
 }
 
-template <int NT, int WAVES, int U, typename OutT>
+template <int MT, int NT, int WAVES, int U, typename OutT>
 arcq_status launch_skinny(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                                  const uint8_t* w_scales, int M, int N, int nbk, float alpha, OutT* y, int64_t ldy,
                                  hipStream_t stream) {
-    hipLaunchKernelGGL((gemm_skinny_kernel<NT, WAVES, U, OutT>), dim3((N + 16 * NT - 1) / (16 * NT)),
+    hipLaunchKernelGGL((gemm_skinny_kernel<MT, NT, WAVES, U, OutT>), dim3((N + 16 * NT - 1) / (16 * NT)),
                        dim3(WAVES * 64), 0, stream, a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy);
     return check_launch("gemm_skinny_kernel");
+}
+
+// Number of runs the reduction dimension is cut into (1: no split).  A function of the shape alone,
+// so that the workspace a caller sizes beforehand matches what the launch uses.  Problems of more
+// than 128 rows with too few 128 x 128 tiles to occupy the chip split K' until about 256 workgroups
+// exist, each run at least four stages (512 k) long.
+int split_k(int64_t M, int64_t N, int64_t Kp) {
+    const int64_t nbk = Kp >> 4;
+    if (M <= 128 || (nbk & 3) != 0 || nbk < 8) return 1;
+    if (((M + 255) / 256) * ((N + 255) / 256) >= 256 || ((M + 127) / 128) * ((N + 255) / 256) >= 192) return 1;
+    const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    if (tiles > 128) return 1;
+    const int64_t nstage = (nbk + 7) >> 3;
+    int64_t splits = std::min<int64_t>(8, (256 + tiles - 1) / tiles);
+    splits = std::min(splits, nstage / 4);
+    return splits < 2 ? 1 : (int)splits;
 }
 
 template <typename OutT>
 arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                          const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, float alpha, OutT* y,
-                         int64_t ldy, hipStream_t stream) {
+                         int64_t ldy, float* workspace, hipStream_t stream) {
     const int nbk = (int)(Kp >> 4);
-    if (M <= 16 && (nbk & 1) == 0 &&
+    if (M <= 128 && (nbk & 1) == 0 &&
         ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
         ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 1) == 0) {
-        // enough waves to keep the weight stream in flight (>= 8 per CU), as few as that allows so
-        // that each wave has several KB to request at once
-        // many weight rows: several tiles per wave share the activation operand; few rows: one
-        // tile per wave so that every CU still gets a workgroup (measured at the decode shapes)
+        // Weight-streaming path.  Enough waves to keep the weight stream in flight, as few as that allows
+        // so that each wave has several KB to request at once: with many weight rows several tiles per
+        // wave share the activation operand; with few, one tile per wave so that every CU still gets a
+        // workgroup (measured at the decode shapes).
         const int64_t tiles = (N + 15) / 16;
-        if (tiles >= 800)
-            return launch_skinny<4, 8, 1>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
-        if (tiles >= 400)
-            return launch_skinny<2, 8, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
-        return launch_skinny<1, 8, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+#define ARCQ_SKINNY_W(MT_, NT_, W_, U_) \
+    return launch_skinny<MT_, NT_, W_, U_>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream)
+#define ARCQ_SKINNY(MT_, NT_, U_) ARCQ_SKINNY_W(MT_, NT_, 8, U_)
+        if (M <= 16) {
+            if (tiles >= 800) ARCQ_SKINNY(1, 4, 1);
+            if (tiles >= 400) ARCQ_SKINNY(1, 2, 2);
+            ARCQ_SKINNY(1, 1, 2);
+        }
+        if (M <= 32) {
+            if (tiles >= 800) ARCQ_SKINNY(2, 2, 1);
+            ARCQ_SKINNY(2, 1, 2);
+        }
+        if (M <= 64) {
+            if (tiles >= 800) ARCQ_SKINNY(4, 2, 1);
+            ARCQ_SKINNY(4, 1, 1);
+        }
+        if (tiles >= 800) ARCQ_SKINNY_W(8, 2, 4, 1);
+        ARCQ_SKINNY(8, 1, 1);
+#undef ARCQ_SKINNY
+#undef ARCQ_SKINNY_W
     }
     const bool offsets_fit = (uint64_t)M * (uint64_t)nbk * 8 < 0xFFFF0000ull && (uint64_t)N * (uint64_t)nbk * 8 < 0xFFFF0000ull;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
@@ -582,7 +687,8 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
         // 2048 x 4096 x 4352 problem; on the large shapes 4 and 8 waves measure the same
         if (t128x256 >= 192)
             return launch_staged<2, 2, 2, 4>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
-        return launch_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+        return launch_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream,
+                                         split_k(M, N, Kp), workspace);
     }
     dim3 grid((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128));
     hipLaunchKernelGGL(gemm_direct_kernel<OutT>, grid, dim3(256), 0, stream, a_codes, a_scales, w_codes, w_scales,
@@ -592,17 +698,21 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
 
 }  // namespace
 
-size_t gemm_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t Kp) {
+    const int splits = split_k(M, N, Kp);
+    return splits > 1 ? (size_t)splits * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
 
 arcq_status launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
                         const uint8_t* w_codes, const uint8_t* w_scales,
                         int64_t M, int64_t N, int64_t Kp, float alpha,
                         void* y, int y_dtype, int64_t ldy,
-                        void*, size_t, hipStream_t stream) {
+                        void* workspace, size_t, hipStream_t stream) {
+    float* ws = static_cast<float*>(workspace);
     if (y_dtype == ARCQ_DTYPE_F16)
         return launch_typed<_Float16>(a_codes, a_scales, w_codes, w_scales, M, N, Kp, alpha,
-                                      static_cast<_Float16*>(y), ldy, stream);
-    return launch_typed<float>(a_codes, a_scales, w_codes, w_scales, M, N, Kp, alpha, static_cast<float*>(y), ldy, stream);
+                                      static_cast<_Float16*>(y), ldy, ws, stream);
+    return launch_typed<float>(a_codes, a_scales, w_codes, w_scales, M, N, Kp, alpha, static_cast<float*>(y), ldy, ws, stream);
 }
 
 }  // namespace arcq

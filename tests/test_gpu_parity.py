@@ -259,6 +259,14 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     (1, 1, 16, 0), (16, 512, 512, 32), (77, 200, 48, 16), (130, 129, 96, 16), (128, 256, 256, 0),
     (257, 131, 1040, 48), (16, 1000, 4096, 256), (300, 77, 2048, 2048),
     (7, 45, 160, 32), (16, 4097, 1008, 16), (3, 16, 14336, 256), (17, 40, 512, 0), (128, 384, 192, 0), (500, 260, 4160, 64),
+    # rows shorter than one 128-k chunk on the weight-streaming kernel (K' = 32, 64, 96)
+    (8, 40, 32, 0), (16, 33, 48, 16), (5, 17, 64, 32),
+    # batched decode: 2, 4 and 8 tiles of 16 activation rows on the weight-streaming kernel, S from 0 to K
+    (20, 300, 512, 32), (32, 1000, 1024, 0), (33, 77, 2048, 2048), (64, 4097, 256, 64), (100, 260, 4160, 64),
+    (128, 45, 160, 32), (17, 14336, 512, 512), (48, 2048, 4096, 1024),
+    # more than 128 rows but few tiles: the reduction dimension is split (8, 8, 4 runs; the last run of the third
+    # ends with a half stage) and the partial results are added by a second kernel; the fourth is too short to split
+    (256, 512, 4096, 256), (300, 260, 4160, 64), (130, 129, 2048, 64), (200, 140, 576, 64),
     # ragged edges in every tile configuration of the staged kernel: 128 x 256 tiles (8 waves), 256 x 256 tiles
     (1990, 4070, 256, 64), (4000, 4100, 128, 64),
 ]
