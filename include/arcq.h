@@ -141,6 +141,31 @@ arcq_status arcq_gemm(const uint8_t* a_codes, const uint8_t* a_scales, float a_t
 arcq_status arcq_check_perm(const int32_t* perm, int64_t K, uint8_t* flags,
                             int* result_host, void* stream);
 
+/*
+ * Offline calibration (Section 3.2 "Adaptive Outlier Identification"), two calls.
+ *
+ * arcq_calib_absmax folds one batch of calibration activations into the running per-channel
+ * statistic: colmax[k] = max(colmax[k], max over rows of |x[m, k]|).  Batches may come in any order.
+ * x       fp16 [M, K], row pitch ldx (same alignment rules as arcq_quantize_act); M may be 0
+ * colmax  in/out, fp32 [K], 4-byte aligned; the caller fills it with zeros before the first batch;
+ *         values stay >= 0.  Concurrent calls on the same colmax are safe (atomic maxima).
+ *
+ * arcq_calib_select turns the statistic into what the quantizer and the weight packer consume:
+ *   perm  out, int32 [K]: channels in ascending order of colmax, equal values by ascending channel
+ *         index, so the outliers are the last positions (the sorting strategy the paper adopts);
+ *   info  out, int32 [4] on the device: {S, S_raw, bit pattern of the layer maximum (fp32),
+ *         bit pattern of tau = 2^-3 * maximum}.  S_raw = number of channels with colmax > tau
+ *         (a channel AT the threshold needs no compensation); S = S_raw rounded up to a multiple
+ *         of 16, at most K (this library works on blocks of 16; the paper does not say).
+ *   S_host  if not NULL the call synchronises the stream and stores S there; if NULL nothing is
+ *         synchronised and the caller reads info in stream order.
+ * colmax must hold finite values >= 0 (what arcq_calib_absmax produces); K as everywhere else.
+ */
+arcq_status arcq_calib_absmax(const void* x, int64_t M, int64_t K, int64_t ldx,
+                              float* colmax, void* stream);
+arcq_status arcq_calib_select(const float* colmax, int64_t K, int32_t* perm, int32_t* info,
+                              int* S_host, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,6 +25,8 @@ SIGNATURES = {
     "arcq_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _vp, _vp, _vp]),
     "arcq_rmsnorm_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _i64, _f32, _vp, _vp, _vp]),
     "arcq_pack_weight": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _vp, _vp, _vp]),
+    "arcq_calib_absmax": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp]),
+    "arcq_calib_select": (ctypes.c_int, [_vp, _i64, _vp, _vp, ctypes.POINTER(ctypes.c_int), _vp]),
     "arcq_gemm_workspace_size": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
     "arcq_gemm": (ctypes.c_int, [_vp, _vp, _f32, _vp, _vp, _f32, _i64, _i64, _i64, _vp, ctypes.c_int, _i64,
                                  _vp, _sz, _vp]),
@@ -144,6 +146,28 @@ def arcq_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_sca
                            _ptr(y), DTYPE_F16 if y.dtype == torch.float16 else DTYPE_F32, ldy,
                            _ptr(workspace) if workspace is not None else None, ws_bytes, _stream()))
     return y
+
+
+def arcq_calib_absmax(x, colmax):
+    """Folds x fp16 [M, K] into the running per-channel abs-max colmax fp32 [K] (zeros before the first batch)."""
+    assert x.is_cuda and x.dtype == torch.float16 and x.dim() == 2 and x.stride(1) == 1
+    assert colmax.is_cuda and colmax.dtype == torch.float32 and colmax.is_contiguous() and colmax.numel() == x.shape[1]
+    M, K = x.shape
+    _check(lib().arcq_calib_absmax(_ptr(x), M, K, x.stride(0) if M > 1 else max(K, x.stride(0)), _ptr(colmax), _stream()))
+    return colmax
+
+
+def arcq_calib_select(colmax, perm=None, info=None):
+    """colmax fp32 [K] -> (perm int32 [K], S, info int32 [4] = {S, S_raw, bits(max), bits(tau)}); synchronises."""
+    assert colmax.is_cuda and colmax.dtype == torch.float32 and colmax.is_contiguous()
+    K = colmax.numel()
+    if perm is None:
+        perm = torch.empty(K, dtype=torch.int32, device=colmax.device)
+    if info is None:
+        info = torch.empty(4, dtype=torch.int32, device=colmax.device)
+    S = ctypes.c_int(-1)
+    _check(lib().arcq_calib_select(_ptr(colmax), K, _ptr(perm), _ptr(info), ctypes.byref(S), _stream()))
+    return perm, S.value, info
 
 
 def prepare_quantize_act(x, perm, S, tensor_scale, codes, scales):

@@ -152,4 +152,26 @@ arcq_status arcq_check_perm(const int32_t* perm, int64_t K, uint8_t* flags, int*
     return launch_check_perm(perm, K, flags, result_host, static_cast<hipStream_t>(stream));
 }
 
+arcq_status arcq_calib_absmax(const void* x, int64_t M, int64_t K, int64_t ldx, float* colmax, void* stream) {
+    clear_error();
+    if (arcq_status st = check_KS(K, 0)) return st;
+    if (M < 0 || M > 0x7FFFFFFF) return fail(ARCQ_BAD_SHAPE, "arcq_calib_absmax: M = %lld out of range", (long long)M);
+    if (ldx < K) return fail(ARCQ_BAD_SHAPE, "arcq_calib_absmax: leading dimension %lld < K = %lld", (long long)ldx, (long long)K);
+    if (M == 0) return ARCQ_OK;
+    if (!x || !colmax) return fail(ARCQ_INVALID_ARG, "arcq_calib_absmax: null pointer");
+    if (!aligned(x, 16) || (ldx % 8) != 0)
+        return fail(ARCQ_BAD_ALIGN, "arcq_calib_absmax: input must be 16-byte aligned with a leading dimension that is a multiple of 8");
+    if (!aligned(colmax, 4)) return fail(ARCQ_BAD_ALIGN, "arcq_calib_absmax: colmax must be 4-byte aligned");
+    return launch_calib_absmax(x, M, K, ldx, colmax, static_cast<hipStream_t>(stream));
+}
+
+arcq_status arcq_calib_select(const float* colmax, int64_t K, int32_t* perm, int32_t* info, int* S_host, void* stream) {
+    clear_error();
+    if (arcq_status st = check_KS(K, 0)) return st;
+    if (!colmax || !perm || !info) return fail(ARCQ_INVALID_ARG, "arcq_calib_select: null pointer");
+    if (!aligned(colmax, 4) || !aligned(perm, 4) || !aligned(info, 4))
+        return fail(ARCQ_BAD_ALIGN, "arcq_calib_select: pointers must be 4-byte aligned");
+    return launch_calib_select(colmax, K, perm, info, S_host, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -31,4 +31,8 @@ arcq_status launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
 arcq_status launch_check_perm(const int32_t* perm, int64_t K, uint8_t* flags,
                               int* result_host, hipStream_t stream);
 
+arcq_status launch_calib_absmax(const void* x, int64_t M, int64_t K, int64_t ldx, float* colmax, hipStream_t stream);
+arcq_status launch_calib_select(const float* colmax, int64_t K, int32_t* perm, int32_t* info, int* S_host,
+                                hipStream_t stream);
+
 }  // namespace arcq

@@ -9,6 +9,7 @@ import pytest
 import torch
 
 from oracle import arcquant as A
+from oracle import calibration as CAL
 from paper_2601_07475_amd import binding as B
 from paper_2601_07475_amd import workloads as wk
 
@@ -376,3 +377,72 @@ def test_config4_qwen32b_mlp_sampled():
 
 def test_config5_llama70b_down_sampled():
     run_full_config("c5_llama70b_down", 48, 384, False)
+
+
+# --------------------------------------------------------------------------------------
+# Offline calibration (Section 3.2 "Adaptive Outlier Identification"): exact integer / bit results
+@pytest.mark.parametrize("M,K", [(1, 16), (7, 48), (33, 512), (100, 1040), (257, 4096), (2048, 4096), (64, 14336),
+                                 (5, 65536), (1000, 8192)])
+def test_calib_absmax_bit_exact(M, K):
+    say(f"calib_absmax M={M} K={K}")
+    wl = wk.Workload("t", M, K, 8, 0, max(1, K // 100), "loguniform20_100", 0.02, 500 + K % 61)
+    X = wk.activations(wl)
+    X[0, 0], X[M - 1, K - 1] = np.float16(-65504.0), np.float16(-0.0)
+    if M > 2:
+        X[:, 3] = (np.arange(M) % 7 * 2.0 ** -24).astype(np.float16)                 # a column of subnormals
+    want = CAL.absmax_update(np.zeros(K, np.float32), X)
+    got = B.arcq_calib_absmax(dev(X), torch.zeros(K, dtype=torch.float32, device="cuda"))
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    # batches in another order, one of them through a strided view, on top of a non-zero running statistic
+    acc = torch.zeros(K, dtype=torch.float32, device="cuda")
+    cut = M // 3
+    wide = torch.full((M - cut, K + 24), 70000.0, dtype=torch.float32, device="cuda").to(torch.float16)
+    wide[:, :K] = dev(X[cut:])
+    B.arcq_calib_absmax(wide[:, :K], acc)
+    B.arcq_calib_absmax(dev(X[:cut]) if cut else torch.empty((0, K), dtype=torch.float16, device="cuda"), acc)
+    B.arcq_calib_absmax(dev(X[:1]), acc)
+    assert np.array_equal(acc.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("K,seed", [(16, 0), (48, 1), (512, 2), (4096, 3), (16400, 4), (65536, 5)])
+def test_calib_select_exact(K, seed):
+    say(f"calib_select K={K}")
+    rng = np.random.default_rng(seed)
+    cm = np.abs(rng.standard_normal(K) * np.exp(rng.standard_normal(K) * 2)).astype(np.float16).astype(np.float32)
+    cm[rng.integers(0, K, K // 4)] = cm[rng.integers(0, K, K // 4)]                   # many ties
+    cases = [cm, np.zeros(K, np.float32), np.full(K, 2.5, np.float32), np.arange(K, dtype=np.float32)[::-1].copy()]
+    edge = np.ones(K, np.float32)
+    edge[K // 2], edge[1] = 8.0, np.nextafter(np.float32(1.0), np.float32(2.0))       # one channel at tau, one just above
+    cases.append(edge)
+    for c in cases:
+        want = CAL.select_outliers(c)
+        perm, S, info = B.arcq_calib_select(dev(c))
+        info = info.cpu().numpy()
+        assert np.array_equal(perm.cpu().numpy(), want["perm"])
+        assert S == want["S"] and info[0] == want["S"] and info[1] == want["S_raw"]
+        assert info[2:].view(np.float32).tolist() == [want["layer_max"], want["tau"]]
+        assert B.arcq_check_perm(perm)
+
+
+def test_calibration_feeds_the_online_path():
+    """abs-max over two batches -> perm, S -> packer, quantizer, GEMM: every stage equals the oracle fed the same way."""
+    say("calibration end to end")
+    wl = wk.Workload("t", 96, 1024, 200, 0, 12, "loguniform20_100", 0.02, 77)
+    X, W = wk.activations(wl), wk.weights(wl)
+    colmax = torch.zeros(wl.K, dtype=torch.float32, device="cuda")
+    for part in (X[:40], X[40:]):
+        B.arcq_calib_absmax(dev(part), colmax)
+    perm, S, _ = B.arcq_calib_select(colmax)
+    want = CAL.select_outliers(CAL.absmax_update(np.zeros(wl.K, np.float32), X))
+    assert S == want["S"] and S > 0 and np.array_equal(perm.cpu().numpy(), want["perm"])
+    sTx, sTw = wk.tensor_scale(X), wk.tensor_scale(W)
+    ac, asc = B.arcq_quantize_act(dev(X), perm, S, sTx)
+    wc, wsc = B.arcq_pack_weight(dev(W), perm, S, sTw)
+    oac, oasc = A.quantize_act(X, want["perm"], S, sTx)
+    owc, owsc = A.pack_weight(W, want["perm"], S, sTw)
+    assert_same_bytes(ac.cpu().numpy(), oac, "activation codes")
+    assert_same_bytes(asc.cpu().numpy(), oasc, "activation scales")
+    assert_same_bytes(wc.cpu().numpy(), owc, "weight codes")
+    assert_same_bytes(wsc.cpu().numpy(), owsc, "weight scales")
+    Y = B.arcq_gemm(ac, asc, sTx, wc, wsc, sTw, out_dtype=torch.float32)
+    assert norm_err(Y.cpu().numpy(), A.gemm(oac, oasc, sTx, owc, owsc, sTw)) <= GEMM_TOL_F32

@@ -122,3 +122,23 @@ def test_check_perm_argument_errors():
     r = ctypes.c_int(0)
     assert B.lib().arcq_check_perm(None, 16, FAKE, ctypes.byref(r), None) == B.INVALID_ARG
     assert B.lib().arcq_check_perm(FAKE, 0, FAKE, ctypes.byref(r), None) == B.BAD_SHAPE
+
+
+def test_calibration_argument_errors():
+    L = B.lib()
+    assert L.arcq_calib_absmax(FAKE, 4, 500, 512, FAKE, None) == B.BAD_SHAPE
+    assert L.arcq_calib_absmax(FAKE, -1, 512, 512, FAKE, None) == B.BAD_SHAPE
+    assert L.arcq_calib_absmax(FAKE, 4, 512, 496, FAKE, None) == B.BAD_SHAPE
+    assert L.arcq_calib_absmax(None, 4, 512, 512, FAKE, None) == B.INVALID_ARG
+    assert L.arcq_calib_absmax(FAKE, 4, 512, 512, None, None) == B.INVALID_ARG
+    assert L.arcq_calib_absmax(ODD, 4, 512, 512, FAKE, None) == B.BAD_ALIGN
+    assert L.arcq_calib_absmax(FAKE, 4, 512, 516, FAKE, None) == B.BAD_ALIGN
+    assert L.arcq_calib_absmax(FAKE, 4, 512, 512, ctypes.c_void_p(0x10002), None) == B.BAD_ALIGN
+    assert L.arcq_calib_absmax(None, 0, 512, 512, None, None) == B.OK                 # empty batch: nothing to do
+    s = ctypes.c_int(0)
+    assert L.arcq_calib_select(FAKE, 40, FAKE, FAKE, ctypes.byref(s), None) == B.BAD_SHAPE
+    assert L.arcq_calib_select(FAKE, B.MAX_K + 16, FAKE, FAKE, ctypes.byref(s), None) == B.BAD_SHAPE
+    assert L.arcq_calib_select(None, 64, FAKE, FAKE, ctypes.byref(s), None) == B.INVALID_ARG
+    assert L.arcq_calib_select(FAKE, 64, None, FAKE, ctypes.byref(s), None) == B.INVALID_ARG
+    assert L.arcq_calib_select(FAKE, 64, FAKE, None, ctypes.byref(s), None) == B.INVALID_ARG
+    assert L.arcq_calib_select(FAKE, 64, ctypes.c_void_p(0x10002), FAKE, ctypes.byref(s), None) == B.BAD_ALIGN
