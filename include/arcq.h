@@ -166,6 +166,37 @@ arcq_status arcq_calib_absmax(const void* x, int64_t M, int64_t K, int64_t ldx,
 arcq_status arcq_calib_select(const float* colmax, int64_t K, int32_t* perm, int32_t* info,
                               int* S_host, void* stream);
 
+/*
+ * MXFP4 variant of the same path (the paper reports the method on MXFP4 as well: Section 4.3
+ * "Generalizability" and the appendix table on INT4 and MXFP4).  Format (Section 3.1 "Block-scaled
+ * Quantization", Appendix A): 32 E2M1 elements per block, one E8M0 scale byte per block (value
+ * 2^(byte - 127)), no tensor scale.  Scale rule (the paper gives none; this is the rule of the OCP
+ * Microscaling specification it cites): shared exponent = floor(log2(block maximum)) - 2; elements round
+ * to nearest even on the E2M1 grid and saturate at 6; an all-zero block gets byte 127.  Residual channels,
+ * their placement and the duplicated weight blocks are those of Section 3.2 with blocks of 32:
+ *   codes  uint8 [rows, K'/2]  (element 2i in bits 0-3 of byte i), 16-byte aligned
+ *   scales uint8 [rows, K'/32] block b < K/32 primary, block K/32 + i the augmented block of primary
+ *                              block (K-S)/32 + i
+ * Shapes: K % 32 == 0, S % 32 == 0, 0 <= S <= K <= ARCQ_MAX_K.  x / w, perm as in the NVFP4 calls, perm
+ * 16-byte aligned.  This is the block format gfx950's scaled FP4 matrix instruction multiplies natively,
+ * so arcq_mx_gemm needs no decode:
+ *   y[m, n] = sum_b 2^(sa[m,b]-127) 2^(sw[n,b]-127) sum_{i<32} qa[m,32b+i] qw[n,32b+i],  fp32 accumulation
+ * (Section 3.2 eq. (2)); Kp % 32 == 0; codes 4-byte aligned (16-byte alignment and Kp % 128 == 0 select the
+ * fast kernel); y as in arcq_gemm.  No workspace.
+ */
+arcq_status arcq_mx_packed_sizes(int64_t rows, int64_t K, int64_t S,
+                                 size_t* codes_bytes, size_t* scales_bytes);
+arcq_status arcq_mx_quantize_act(const void* x, int64_t M, int64_t K, int64_t ldx,
+                                 const int32_t* perm, int64_t S,
+                                 uint8_t* codes, uint8_t* scales, void* stream);
+arcq_status arcq_mx_pack_weight(const void* w, int64_t N, int64_t K, int64_t ldw,
+                                const int32_t* perm, int64_t S,
+                                uint8_t* codes, uint8_t* scales, void* stream);
+arcq_status arcq_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
+                         const uint8_t* w_codes, const uint8_t* w_scales,
+                         int64_t M, int64_t N, int64_t Kp,
+                         void* y, int y_dtype, int64_t ldy, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

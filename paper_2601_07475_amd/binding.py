@@ -25,6 +25,10 @@ SIGNATURES = {
     "arcq_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _vp, _vp, _vp]),
     "arcq_rmsnorm_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _i64, _f32, _vp, _vp, _vp]),
     "arcq_pack_weight": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _vp, _vp, _vp]),
+    "arcq_mx_packed_sizes": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
+    "arcq_mx_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
+    "arcq_mx_pack_weight": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
+    "arcq_mx_gemm": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, ctypes.c_int, _i64, _vp]),
     "arcq_calib_absmax": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp]),
     "arcq_calib_select": (ctypes.c_int, [_vp, _i64, _vp, _vp, ctypes.POINTER(ctypes.c_int), _vp]),
     "arcq_gemm_workspace_size": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
@@ -168,6 +172,51 @@ def arcq_calib_select(colmax, perm=None, info=None):
     S = ctypes.c_int(-1)
     _check(lib().arcq_calib_select(_ptr(colmax), K, _ptr(perm), _ptr(info), ctypes.byref(S), _stream()))
     return perm, S.value, info
+
+
+def _mx_quantize(fn, x, perm, S, codes=None, scales=None):
+    assert x.is_cuda and x.dtype == torch.float16 and x.dim() == 2 and x.stride(1) == 1
+    assert perm.is_cuda and perm.dtype == torch.int32 and perm.is_contiguous()
+    rows, K = x.shape
+    if perm.numel() != K:
+        raise ArcqError(BAD_SHAPE, "perm must have K entries")
+    cb, sb = _sz(0), _sz(0)
+    _check(lib().arcq_mx_packed_sizes(rows, K, S, ctypes.byref(cb), ctypes.byref(sb)))
+    Kp = K + S
+    if codes is None:
+        codes = torch.empty((rows, Kp // 2), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows, Kp // 32), dtype=torch.uint8, device=x.device)
+    assert codes.numel() == cb.value and scales.numel() == sb.value and codes.is_contiguous() and scales.is_contiguous()
+    ldx = x.stride(0) if rows > 1 else max(K, x.stride(0))
+    _check(fn(_ptr(x), rows, K, ldx, _ptr(perm), S, _ptr(codes), _ptr(scales), _stream()))
+    return codes, scales
+
+
+def arcq_mx_quantize_act(x, perm, S, codes=None, scales=None):
+    """MXFP4: x fp16 [M, K] -> (codes uint8 [M, K'/2], scales uint8 [M, K'/32])."""
+    return _mx_quantize(lib().arcq_mx_quantize_act, x, perm, S, codes, scales)
+
+
+def arcq_mx_pack_weight(w, perm, S, codes=None, scales=None):
+    return _mx_quantize(lib().arcq_mx_pack_weight, w, perm, S, codes, scales)
+
+
+def arcq_mx_gemm(a_codes, a_scales, w_codes, w_scales, out_dtype=torch.float16, y=None):
+    """MXFP4: y[M, N] = deq(A) deq(W)^T over K' on the scaled FP4 matrix instruction; returns y."""
+    for t in (a_codes, a_scales, w_codes, w_scales):
+        assert t.is_cuda and t.dtype == torch.uint8 and t.is_contiguous()
+    M, N = a_codes.shape[0], w_codes.shape[0]
+    Kp = a_codes.shape[1] * 2
+    if w_codes.shape[1] * 2 != Kp or a_scales.shape != (M, Kp // 32) or w_scales.shape != (N, Kp // 32):
+        raise ArcqError(BAD_SHAPE, "operand shapes disagree on K'")
+    if y is None:
+        y = torch.empty((M, N), dtype=out_dtype, device=a_codes.device)
+    assert y.shape == (M, N) and y.stride(1) == 1 and y.dtype in (torch.float16, torch.float32)
+    ldy = y.stride(0) if M > 1 else max(N, y.stride(0))
+    _check(lib().arcq_mx_gemm(_ptr(a_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), M, N, Kp, _ptr(y),
+                              DTYPE_F16 if y.dtype == torch.float16 else DTYPE_F32, ldy, _stream()))
+    return y
 
 
 def prepare_quantize_act(x, perm, S, tensor_scale, codes, scales):

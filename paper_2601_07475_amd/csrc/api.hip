@@ -65,6 +65,29 @@ arcq_status quantize_entry(int mode, const char* who, const void* x, int64_t row
                            static_cast<hipStream_t>(stream));
 }
 
+arcq_status check_KS_mx(int64_t K, int64_t S) {
+    if (K <= 0 || (K % 32) != 0) return fail(ARCQ_BAD_SHAPE, "K = %lld: must be > 0 and a multiple of 32", (long long)K);
+    if (K > ARCQ_MAX_K) return fail(ARCQ_BAD_SHAPE, "K = %lld exceeds ARCQ_MAX_K = %d", (long long)K, ARCQ_MAX_K);
+    if (S < 0 || S > K || (S % 32) != 0)
+        return fail(ARCQ_BAD_SHAPE, "S = %lld: must satisfy 0 <= S <= K and S %% 32 == 0", (long long)S);
+    return ARCQ_OK;
+}
+
+arcq_status mx_quantize_entry(int mode, const char* who, const void* x, int64_t rows, int64_t K, int64_t ldx,
+                              const int32_t* perm, int64_t S, uint8_t* codes, uint8_t* scales, void* stream) {
+    clear_error();
+    if (arcq_status st = check_KS_mx(K, S)) return st;
+    if (rows < 0 || rows > 0x7FFFFFFF) return fail(ARCQ_BAD_SHAPE, "%s: rows = %lld out of range", who, (long long)rows);
+    if (ldx < K) return fail(ARCQ_BAD_SHAPE, "%s: leading dimension %lld < K = %lld", who, (long long)ldx, (long long)K);
+    if (rows == 0) return ARCQ_OK;
+    if (!x || !perm || !codes || !scales) return fail(ARCQ_INVALID_ARG, "%s: null pointer", who);
+    if (!aligned(x, 16) || (ldx % 8) != 0)
+        return fail(ARCQ_BAD_ALIGN, "%s: input must be 16-byte aligned with a leading dimension that is a multiple of 8", who);
+    if (!aligned(codes, 16)) return fail(ARCQ_BAD_ALIGN, "%s: codes must be 16-byte aligned", who);
+    if (!aligned(perm, 16)) return fail(ARCQ_BAD_ALIGN, "%s: perm must be 16-byte aligned", who);
+    return launch_mx_quantize(mode, x, rows, K, ldx, perm, S, codes, scales, static_cast<hipStream_t>(stream));
+}
+
 }  // namespace
 }  // namespace arcq
 
@@ -172,6 +195,42 @@ arcq_status arcq_calib_select(const float* colmax, int64_t K, int32_t* perm, int
     if (!aligned(colmax, 4) || !aligned(perm, 4) || !aligned(info, 4))
         return fail(ARCQ_BAD_ALIGN, "arcq_calib_select: pointers must be 4-byte aligned");
     return launch_calib_select(colmax, K, perm, info, S_host, static_cast<hipStream_t>(stream));
+}
+
+arcq_status arcq_mx_packed_sizes(int64_t rows, int64_t K, int64_t S, size_t* codes_bytes, size_t* scales_bytes) {
+    clear_error();
+    if (arcq_status st = check_KS_mx(K, S)) return st;
+    if (rows < 0) return fail(ARCQ_BAD_SHAPE, "rows = %lld < 0", (long long)rows);
+    if (!codes_bytes || !scales_bytes) return fail(ARCQ_INVALID_ARG, "null output pointer");
+    *codes_bytes = (size_t)rows * (size_t)(K + S) / 2;
+    *scales_bytes = (size_t)rows * (size_t)(K + S) / 32;
+    return ARCQ_OK;
+}
+
+arcq_status arcq_mx_quantize_act(const void* x, int64_t M, int64_t K, int64_t ldx, const int32_t* perm, int64_t S,
+                                 uint8_t* codes, uint8_t* scales, void* stream) {
+    return mx_quantize_entry(0, "arcq_mx_quantize_act", x, M, K, ldx, perm, S, codes, scales, stream);
+}
+
+arcq_status arcq_mx_pack_weight(const void* w, int64_t N, int64_t K, int64_t ldw, const int32_t* perm, int64_t S,
+                                uint8_t* codes, uint8_t* scales, void* stream) {
+    return mx_quantize_entry(1, "arcq_mx_pack_weight", w, N, K, ldw, perm, S, codes, scales, stream);
+}
+
+arcq_status arcq_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
+                         int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy, void* stream) {
+    clear_error();
+    if (M < 0 || N < 0 || M > 0x7FFFFFFF || N > 0x7FFFFFFF)
+        return fail(ARCQ_BAD_SHAPE, "M = %lld, N = %lld out of range", (long long)M, (long long)N);
+    if (Kp <= 0 || (Kp % 32) != 0 || Kp > 2 * (int64_t)ARCQ_MAX_K)
+        return fail(ARCQ_BAD_SHAPE, "K' = %lld: must be a positive multiple of 32, at most %d", (long long)Kp, 2 * ARCQ_MAX_K);
+    if (y_dtype != ARCQ_DTYPE_F16 && y_dtype != ARCQ_DTYPE_F32) return fail(ARCQ_INVALID_ARG, "y_dtype = %d", y_dtype);
+    if (ldy < N) return fail(ARCQ_BAD_SHAPE, "ldy = %lld < N = %lld", (long long)ldy, (long long)N);
+    if (M == 0 || N == 0) return ARCQ_OK;
+    if (!a_codes || !a_scales || !w_codes || !w_scales || !y) return fail(ARCQ_INVALID_ARG, "arcq_mx_gemm: null pointer");
+    if (!aligned(a_codes, 4) || !aligned(w_codes, 4)) return fail(ARCQ_BAD_ALIGN, "arcq_mx_gemm: codes must be 4-byte aligned");
+    if (!aligned(y, 4)) return fail(ARCQ_BAD_ALIGN, "arcq_mx_gemm: y must be 4-byte aligned");
+    return launch_mx_gemm(a_codes, a_scales, w_codes, w_scales, M, N, Kp, y, y_dtype, ldy, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

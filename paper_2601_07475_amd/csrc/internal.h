@@ -35,4 +35,11 @@ arcq_status launch_calib_absmax(const void* x, int64_t M, int64_t K, int64_t ldx
 arcq_status launch_calib_select(const float* colmax, int64_t K, int32_t* perm, int32_t* info, int* S_host,
                                 hipStream_t stream);
 
+// MXFP4 variant (blocks of 32, E8M0 scales, no tensor scale)
+arcq_status launch_mx_quantize(int mode, const void* x, int64_t rows, int64_t K, int64_t ldx, const int32_t* perm,
+                               int64_t S, uint8_t* codes, uint8_t* scales, hipStream_t stream);
+arcq_status launch_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                           const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy,
+                           hipStream_t stream);
+
 }  // namespace arcq

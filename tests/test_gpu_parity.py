@@ -10,6 +10,7 @@ import torch
 
 from oracle import arcquant as A
 from oracle import calibration as CAL
+from oracle import mxfp4 as MX
 from paper_2601_07475_amd import binding as B
 from paper_2601_07475_amd import workloads as wk
 
@@ -446,3 +447,109 @@ def test_calibration_feeds_the_online_path():
     assert_same_bytes(wsc.cpu().numpy(), owsc, "weight scales")
     Y = B.arcq_gemm(ac, asc, sTx, wc, wsc, sTw, out_dtype=torch.float32)
     assert norm_err(Y.cpu().numpy(), A.gemm(oac, oasc, sTx, owc, owsc, sTw)) <= GEMM_TOL_F32
+
+
+# --------------------------------------------------------------------------------------
+# MXFP4 variant of the path: codes and scale bytes bit-exact, GEMM on the scaled FP4 matrix instruction
+def gpu_mx_quantize(fn, X, perm, S):
+    rows, K = X.shape
+    Kp = K + S
+    raw_c, codes = guarded_empty((rows, Kp // 2))
+    raw_s, scales = guarded_empty((rows, Kp // 32))
+    fn(dev(X), dev(perm.astype(np.int32)), S, codes=codes, scales=scales)
+    torch.cuda.synchronize()
+    assert guards_intact(raw_c, rows * Kp // 2) and guards_intact(raw_s, rows * Kp // 32)
+    return codes.cpu().numpy(), scales.cpu().numpy()
+
+
+MX_SHAPES = [(1, 32, 0), (3, 32, 32), (5, 96, 32), (16, 512, 64), (33, 1056, 1056), (67, 4096, 256), (9, 5120, 512),
+             (5, 14336, 256), (3, 28672, 1024), (2, 40000, 32), (2, 65536, 2048)]
+
+
+@pytest.mark.parametrize("M,K,S", MX_SHAPES)
+def test_mx_quantize_act_bit_exact(M, K, S):
+    say(f"mx_quantize_act parity M={M} K={K} S={S}")
+    c = rand_case(M, K, 8, S, seed=700 + K % 97)
+    want_c, want_s = MX.quantize_act(c["X"], c["perm"], S)
+    got_c, got_s = gpu_mx_quantize(B.arcq_mx_quantize_act, c["X"], c["perm"], S)
+    assert_same_bytes(got_s, want_s, "scales")
+    assert_same_bytes(got_c, want_c, "codes")
+    want_c, want_s = MX.pack_weight(c["X"], c["perm"], S)            # the packer on the same tensor
+    got_c, got_s = gpu_mx_quantize(B.arcq_mx_pack_weight, c["X"], c["perm"], S)
+    assert_same_bytes(got_s, want_s, "weight scales")
+    assert_same_bytes(got_c, want_c, "weight codes")
+
+
+def test_mx_quantize_every_fp16_value():
+    say("mx_quantize_act over every finite fp16 value")
+    bits = np.arange(0x10000, dtype=np.uint32)
+    vals = bits[(bits & 0x7C00) != 0x7C00].astype(np.uint16).view(np.float16)
+    rng = np.random.default_rng(6)
+    K = 512
+    rows = [vals[rng.permutation(len(vals))][: len(vals) // K * K].reshape(-1, K) for _ in range(2)]
+    srt = np.sort(vals.astype(np.float32)).astype(np.float16)
+    rows.append(srt[: len(srt) // K * K].reshape(-1, K))
+    rows.append(np.zeros((2, K), np.float16))
+    rows[-1][1, ::3] = np.float16(-0.0)
+    X = np.concatenate(rows).astype(np.float16)
+    perm = rng.permutation(K).astype(np.int32)
+    want_c, want_s = MX.quantize_act(X, perm, K)
+    got_c, got_s = gpu_mx_quantize(B.arcq_mx_quantize_act, X, perm, K)
+    assert_same_bytes(got_s, want_s, "scales")
+    assert_same_bytes(got_c, want_c, "codes")
+
+
+MX_GEMM_SHAPES = [  # M, N, K, S: fallback kernel (K' % 128 != 0), every staged tile configuration, ragged edges
+    (1, 1, 32, 0), (77, 200, 64, 32), (130, 129, 96, 32), (16, 512, 512, 0), (128, 256, 256, 0), (257, 131, 1024, 0),
+    (300, 77, 2048, 2048), (500, 260, 4096, 128), (16, 1000, 4096, 256), (1990, 4070, 256, 128), (4000, 4100, 96, 32),
+]
+
+
+@pytest.mark.parametrize("M,N,K,S", MX_GEMM_SHAPES)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+def test_mx_gemm_parity(M, N, K, S, dtype):
+    say(f"mx_gemm parity M={M} N={N} K={K} S={S} {dtype}")
+    c = rand_case(M, K, N, S, seed=800 + M + N)
+    ac, asc = MX.quantize_act(c["X"], c["perm"], S)
+    wc, wsc = MX.pack_weight(c["W"], c["perm"], S)
+    Yref = MX.gemm(ac, asc, wc, wsc)
+    Y = B.arcq_mx_gemm(dev(ac), dev(asc), dev(wc), dev(wsc), out_dtype=dtype)
+    torch.cuda.synchronize()
+    err = norm_err(Y.float().cpu().numpy(), Yref)
+    say(f"   normalised max error {err:.3e}")
+    assert err <= (GEMM_TOL_F16 if dtype == torch.float16 else GEMM_TOL_F32)
+
+
+def test_mx_gemm_extreme_scales():
+    """Scale bytes from the ends of what fp16 data can produce, every code value, strided output with a guard."""
+    say("mx_gemm extreme scales")
+    rng = np.random.default_rng(3)
+    M, N, Kp = 40, 72, 256
+    ac = rng.integers(0, 256, (M, Kp // 2), dtype=np.uint8)
+    wc = rng.integers(0, 256, (N, Kp // 2), dtype=np.uint8)
+    asc = rng.choice(np.array([101, 102, 127, 139, 140], np.uint8), (M, Kp // 32))
+    wsc = rng.choice(np.array([101, 110, 127, 130, 140], np.uint8), (N, Kp // 32))
+    Yref = MX.gemm(ac, asc, wc, wsc)
+    wide = torch.full((M, N + 8), 7.0, dtype=torch.float32, device="cuda")
+    B.arcq_mx_gemm(dev(ac), dev(asc), dev(wc), dev(wsc), y=wide[:, :N])
+    out = wide.cpu().numpy()
+    assert norm_err(out[:, :N], Yref) <= GEMM_TOL_F32 and np.all(out[:, N:] == 7.0)
+
+
+def test_mx_full_size_llama8b_qproj():
+    """The bench's MXFP4 workload at full size: quantizer bit-exact, GEMM on sampled rows."""
+    say("mx path full size 2048 x 4096 x 4096, S = 256")
+    c = wk.make_case(wk.WORKLOADS["c2_llama8b_q"])
+    X, W, perm, S = c["X"], c["W"], c["perm"], c["S"]
+    want_c, want_s = MX.quantize_act(X, perm, S)
+    ac, asc = B.arcq_mx_quantize_act(dev(X), dev(perm), S)
+    assert_same_bytes(asc.cpu().numpy(), want_s, "scales")
+    assert_same_bytes(ac.cpu().numpy(), want_c, "codes")
+    wc, wsc = B.arcq_mx_pack_weight(dev(W), dev(perm), S)
+    owc, owsc = MX.pack_weight(W, perm, S)
+    assert_same_bytes(wc.cpu().numpy(), owc, "weight codes")
+    assert_same_bytes(wsc.cpu().numpy(), owsc, "weight scales")
+    Y = B.arcq_mx_gemm(ac, asc, wc, wsc).float().cpu().numpy()
+    rows = np.random.default_rng(1).choice(X.shape[0], 48, replace=False)
+    Yref = MX.gemm(want_c[rows], want_s[rows], owc, owsc)
+    assert norm_err(Y[rows], Yref) <= GEMM_TOL_F16

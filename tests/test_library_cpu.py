@@ -142,3 +142,23 @@ def test_calibration_argument_errors():
     assert L.arcq_calib_select(FAKE, 64, None, FAKE, ctypes.byref(s), None) == B.INVALID_ARG
     assert L.arcq_calib_select(FAKE, 64, FAKE, None, ctypes.byref(s), None) == B.INVALID_ARG
     assert L.arcq_calib_select(FAKE, 64, ctypes.c_void_p(0x10002), FAKE, ctypes.byref(s), None) == B.BAD_ALIGN
+
+
+def test_mx_argument_errors():
+    L = B.lib()
+    for fn in (L.arcq_mx_quantize_act, L.arcq_mx_pack_weight):
+        assert fn(FAKE, 4, 528, 528, FAKE, 32, FAKE, FAKE, None) == B.BAD_SHAPE          # K % 32
+        assert fn(FAKE, 4, 512, 512, FAKE, 16, FAKE, FAKE, None) == B.BAD_SHAPE          # S % 32
+        assert fn(FAKE, 4, 512, 496, FAKE, 32, FAKE, FAKE, None) == B.BAD_SHAPE
+        assert fn(None, 4, 512, 512, FAKE, 32, FAKE, FAKE, None) == B.INVALID_ARG
+        assert fn(FAKE, 4, 512, 512, FAKE, 32, ctypes.c_void_p(0x10008), FAKE, None) == B.BAD_ALIGN
+        assert fn(FAKE, 4, 512, 512, ctypes.c_void_p(0x10004), 32, FAKE, FAKE, None) == B.BAD_ALIGN
+        assert fn(None, 0, 512, 512, None, 32, None, None, None) == B.OK
+    cb, sb = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    assert L.arcq_mx_packed_sizes(10, 512, 64, ctypes.byref(cb), ctypes.byref(sb)) == B.OK
+    assert (cb.value, sb.value) == (10 * 576 // 2, 10 * 576 // 32)
+    mg = lambda M=4, N=8, Kp=64, ac=FAKE, y=FAKE, dt=0, ldy=8: L.arcq_mx_gemm(ac, FAKE, FAKE, FAKE, M, N, Kp, y, dt, ldy, None)
+    assert mg(Kp=48) == B.BAD_SHAPE and mg(Kp=0) == B.BAD_SHAPE and mg(ldy=4) == B.BAD_SHAPE
+    assert mg(dt=9) == B.INVALID_ARG and mg(ac=None) == B.INVALID_ARG
+    assert mg(ac=ctypes.c_void_p(0x10002)) == B.BAD_ALIGN and mg(y=ctypes.c_void_p(0x10002)) == B.BAD_ALIGN
+    assert mg(M=0, ac=None, y=None) == B.OK
