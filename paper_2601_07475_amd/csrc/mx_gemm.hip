@@ -11,6 +11,8 @@
 #include "internal.h"
 #include "lds_dma.h"
 
+#include <type_traits>
+
 namespace arcq {
 
 namespace {
@@ -25,32 +27,39 @@ __device__ __forceinline__ float16v mfma_mx(const uint4& a, const uint4& b, cons
                   : __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, vb, c, 4, 4, 2, sa, 2, sb);
 }
 
-// Staged kernel for K' % 128 == 0.  A stage is 128 k: per row 64 bytes of codes (four 16-byte pieces =
-// four MX blocks) and 4 scale bytes; stages travel global -> LDS with global_load_lds through a ring of
-// three buffers, one barrier per stage.  LDS layout of one stage: A codes [BM][64] | W codes [BN][64] |
-// A scales [BM] dwords | W scales [BN] dwords (regions padded to whole workgroup-wide copies).  The four
-// pieces of a row are stored XOR-swizzled with (row >> 1) & 3, applied by choosing which global piece a
-// lane fetches (a wave-wide copy writes lane l to base + 16 l).
+// Staged kernel for K' % 128 == 0.  A unit is 256 k: per row 128 bytes of codes (eight 16-byte pieces =
+// eight MX blocks) and 8 scale bytes, so that a copy instruction asks for whole 128-byte cache lines
+// (8 lanes per row): the texture-address unit of a CU spends about 34 cycles on a copy that touches
+// sixteen 64-byte segments and 17.5 on one that touches eight full lines (measured), and with FP4
+// MFMAs the copies of a 256 x 256 tile would otherwise take as long as its arithmetic.  Units travel
+// global -> LDS with global_load_lds through a ring of NUNIT buffers (2 for the 256 x 256 tile: 2 x 68 KB),
+// one barrier per unit.  LDS layout of one unit: A codes [BM][128] | W codes [BN][128] | A scales [BM][8] |
+// W scales [BN][8] (regions padded to whole workgroup-wide copies).  The eight pieces of a row are stored
+// XOR-swizzled with row & 7 (a 16-byte read by 8 consecutive rows then covers all 32 banks), applied by
+// choosing which global piece a lane fetches (a wave-wide copy writes lane l to base + 16 l).
+// When K' is an odd multiple of 128 the last unit is half a unit: its copies re-fetch the first half
+// for the missing second half (never used, in bounds).
 template <int WM, int WN, int GM, int GN>
 struct MxCfg {
     static constexpr int BM = 32 * WM * GM, BN = 32 * WN * GN;
     static constexpr int NT = 64 * GM * GN;
-    static constexpr int NA = (BM * 4 + NT - 1) / NT, NW = (BN * 4 + NT - 1) / NT;
-    static constexpr int NAS = (BM + NT - 1) / NT, NWS = (BN + NT - 1) / NT;
+    static constexpr int NA = (BM * 8 + NT - 1) / NT, NW = (BN * 8 + NT - 1) / NT;       // 16-byte pieces of codes
+    static constexpr int NAS = (BM * 2 + NT - 1) / NT, NWS = (BN * 2 + NT - 1) / NT;     // 4-byte words of scales
     static constexpr int NDMA = NA + NW + NAS + NWS;
     static constexpr int A_CODES = 0;
     static constexpr int W_CODES = NA * NT * 16;
     static constexpr int A_SCALES = W_CODES + NW * NT * 16;
     static constexpr int W_SCALES = A_SCALES + NAS * NT * 4;
-    static constexpr int STAGE_BYTES = W_SCALES + NWS * NT * 4;
-    static constexpr int NSTAGE = 3;
-    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+    static constexpr int UNIT_BYTES = W_SCALES + NWS * NT * 4;
+    static constexpr int NUNIT = (160 * 1024) / UNIT_BYTES >= 3 ? 3 : 2;
+    static constexpr int LDS_BYTES = NUNIT * UNIT_BYTES;
+    static_assert(NDMA * (NUNIT - 1) < 64, "the counted wait needs the copies of NUNIT - 1 units to fit the counter");
 };
 
 template <int WM, int WN, int GM, int GN, typename OutT>
 __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
-    const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N, int nstage,
+    const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N, int nb,
     OutT* __restrict__ y, int64_t ldy, int tiles_m, int tiles_n) {
     using C = MxCfg<WM, WN, GM, GN>;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -73,39 +82,48 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
     const int wg_m0 = tile_m * C::BM, wg_n0 = tile_n * C::BN;
     const int wrow0 = (wave / GN) * (32 * WM), wcol0 = (wave % GN) * (32 * WN);
 
-    // ---- copies: thread -> (row, piece) of a workgroup-wide copy
-    const uint32_t cpitch = (uint32_t)nstage * 64u, spitch = (uint32_t)nstage * 4u;
-    const uint32_t lp = (uint32_t)((tid & 3) ^ ((tid >> 3) & 3)) * 16u;      // global piece this lane fetches
-    const int crow = tid >> 2;
+    const bool has_half = (nb & 7) != 0;                    // nb % 8 == 4
+    const int nunit = (nb >> 3) + (has_half ? 1 : 0);
+
+    // ---- copies: thread -> (row, piece) of a workgroup-wide copy; 8 lanes fetch one row's 128 bytes
+    const uint32_t cpitch = (uint32_t)nb * 16u, spitch = (uint32_t)nb;
+    const uint32_t lp = (uint32_t)((tid & 7) ^ ((tid >> 3) & 7));               // global piece this lane fetches
+    const int crow = tid >> 3, srow = tid >> 1;
     const uint32_t wave_slot = __builtin_amdgcn_readfirstlane((uint32_t)(tid & ~63));
     const uint32_t lds0 = lds_address(lds);
-    auto issue_one = [&](int d, int stage, int buf) {
-        const uint32_t base = lds0 + buf * C::STAGE_BYTES;
+    auto issue_one = [&](int d, int unit, int buf) {
+        const uint32_t base = lds0 + buf * C::UNIT_BYTES;
         constexpr int NA = C::NA, NW = C::NW, NAS = C::NAS, NT = C::NT;
+        const bool half = has_half && unit == nunit - 1;
+        const uint32_t oc = (uint32_t)unit * 128u + (half ? (lp & 3u) : lp) * 16u;
+        const uint32_t os = (uint32_t)unit * 8u + (half ? 0u : (uint32_t)(tid & 1) * 4u);
         // rows past the edge of the operand re-read its last row (never stored)
         if (d < NA) {
-            const uint32_t row = (uint32_t)min(wg_m0 + d * (NT / 4) + crow, M - 1);
-            dma16(a_codes, row * cpitch + (uint32_t)stage * 64u + lp, base + C::A_CODES + 16u * (d * NT + wave_slot));
+            const uint32_t row = (uint32_t)min(wg_m0 + d * (NT / 8) + crow, M - 1);
+            dma16(a_codes, row * cpitch + oc, base + C::A_CODES + 16u * (d * NT + wave_slot));
         } else if (d < NA + NW) {
             const int p = d - NA;
-            const uint32_t row = (uint32_t)min(wg_n0 + p * (NT / 4) + crow, N - 1);
-            dma16(w_codes, row * cpitch + (uint32_t)stage * 64u + lp, base + C::W_CODES + 16u * (p * NT + wave_slot));
+            const uint32_t row = (uint32_t)min(wg_n0 + p * (NT / 8) + crow, N - 1);
+            dma16(w_codes, row * cpitch + oc, base + C::W_CODES + 16u * (p * NT + wave_slot));
         } else if (d < NA + NW + NAS) {
             const int p = d - NA - NW;
-            const uint32_t row = (uint32_t)min(wg_m0 + p * NT + tid, M - 1);
-            dma4(a_scales, row * spitch + (uint32_t)stage * 4u, base + C::A_SCALES + 4u * (p * NT + wave_slot));
+            const uint32_t row = (uint32_t)min(wg_m0 + p * (NT / 2) + srow, M - 1);
+            dma4(a_scales, row * spitch + os, base + C::A_SCALES + 4u * (p * NT + wave_slot));
         } else {
             const int p = d - NA - NW - NAS;
-            const uint32_t row = (uint32_t)min(wg_n0 + p * NT + tid, N - 1);
-            dma4(w_scales, row * spitch + (uint32_t)stage * 4u, base + C::W_SCALES + 4u * (p * NT + wave_slot));
+            const uint32_t row = (uint32_t)min(wg_n0 + p * (NT / 2) + srow, N - 1);
+            dma4(w_scales, row * spitch + os, base + C::W_SCALES + 4u * (p * NT + wave_slot));
         }
     };
 
-    // ---- LDS read offsets of this lane: piece 2t + h of its rows, physical position XOR (row >> 1) & 3
-    const uint32_t swz = (uint32_t)(r >> 1) & 3u;
-    const uint32_t rd_a = C::A_CODES + (wrow0 + r) * 64, rd_w = C::W_CODES + (wcol0 + r) * 64;
-    const uint32_t rd_as = C::A_SCALES + (wrow0 + r) * 4, rd_ws = C::W_SCALES + (wcol0 + r) * 4;
-    const uint32_t pc[2] = {16u * ((uint32_t)h ^ swz), 16u * ((2u + (uint32_t)h) ^ swz)};
+    // ---- LDS read offsets of this lane: k-step t of a unit takes piece 2t + h of its rows, stored at
+    // physical position (2t + h) ^ (row & 7); row & 7 = r & 7 because the other terms are multiples of 32
+    const uint32_t swz = (uint32_t)r & 7u;
+    const uint32_t rd_a = C::A_CODES + (wrow0 + r) * 128, rd_w = C::W_CODES + (wcol0 + r) * 128;
+    const uint32_t rd_as = C::A_SCALES + (wrow0 + r) * 8, rd_ws = C::W_SCALES + (wcol0 + r) * 8;
+    uint32_t pc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) pc[t] = 16u * ((uint32_t)(2 * t + h) ^ swz);
 
     float16v acc[WM][WN];
 #pragma unroll
@@ -115,66 +133,90 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    uint4 fa[2][WM], fw[2][WN];             // fragments of k-step 0 and 1 of the current stage
-    int sa[WM], sw[WN], sa_n[WM], sw_n[WN]; // scale registers (already shifted so that byte 2t is the lane's)
-    auto read_codes = [&](int t, const uint8_t* st) {
+    uint4 fa[2][WM], fw[2][WN];             // fragments of the k-step being computed and of the next one
+    uint2 sa[WM], sw[WN], sa_n[WM], sw_n[WN];   // scale bytes of the unit (.x: blocks 0-3, .y: 4-7), shifted so
+                                                // that bytes 0 and 2 of each word are this lane's
+    auto read_codes = [&](int slot, int t, const uint8_t* st) {
 #pragma unroll
-        for (int i = 0; i < WM; ++i) fa[t][i] = *reinterpret_cast<const uint4*>(st + rd_a + i * 2048 + pc[t]);
+        for (int i = 0; i < WM; ++i) fa[slot][i] = *reinterpret_cast<const uint4*>(st + rd_a + i * 4096 + pc[t]);
 #pragma unroll
-        for (int j = 0; j < WN; ++j) fw[t][j] = *reinterpret_cast<const uint4*>(st + rd_w + j * 2048 + pc[t]);
+        for (int j = 0; j < WN; ++j) fw[slot][j] = *reinterpret_cast<const uint4*>(st + rd_w + j * 4096 + pc[t]);
     };
-    auto read_scales = [&](const uint8_t* st, int (&da)[WM], int (&dw)[WN]) {
+    auto read_scales = [&](const uint8_t* st, uint2 (&da)[WM], uint2 (&dw)[WN]) {
 #pragma unroll
-        for (int i = 0; i < WM; ++i) da[i] = (int)(*reinterpret_cast<const uint32_t*>(st + rd_as + i * 128) >> (8 * h));
+        for (int i = 0; i < WM; ++i) {
+            const uint2 v = *reinterpret_cast<const uint2*>(st + rd_as + i * 256);
+            da[i] = make_uint2(v.x >> (8 * h), v.y >> (8 * h));
+        }
 #pragma unroll
-        for (int j = 0; j < WN; ++j) dw[j] = (int)(*reinterpret_cast<const uint32_t*>(st + rd_ws + j * 128) >> (8 * h));
-    };
-    auto mfmas = [&](int t, int first, int count) {     // MFMAs first .. first+count-1 of k-step t (row-major over i, j)
-#pragma unroll
-        for (int q = first; q < first + count; ++q) {
-            const int i = q / WN, j = q % WN;
-            // weights as the row operand: see store_tile_swapped
-            acc[i][j] = mfma_mx(fw[t][j], fa[t][i], acc[i][j], sw[j], sa[i], t);
+        for (int j = 0; j < WN; ++j) {
+            const uint2 v = *reinterpret_cast<const uint2*>(st + rd_ws + j * 256);
+            dw[j] = make_uint2(v.x >> (8 * h), v.y >> (8 * h));
         }
     };
 
-    // ---- pipeline: the copies of stage s+2 are issued during stage s (its buffer was last read in stage
-    // s-1, which every wave left before the barrier inside stage s-1); the barrier that opens stage s+1 and the
-    // reads of its first fragments sit before the last half of the MFMAs of stage s.
-    constexpr int HALF = (WM * WN) / 2;
-    issue_one(0, 0, 0);
-#pragma unroll
-    for (int d = 1; d < C::NDMA; ++d) issue_one(d, 0, 0);
-#pragma unroll
-    for (int d = 0; d < C::NDMA; ++d) issue_one(d, min(1, nstage - 1), 1);
-    wait_vmcnt<C::NDMA>();
-    wg_barrier();
-    read_codes(0, lds);
-    read_scales(lds, sa, sw);
+    // ---- pipeline, scheduled by hand (one wave per SIMD: nothing else hides a stall).  A unit is
+    // NSTEPS WM WN MFMAs.  The copies of unit u + NUNIT - 1 are issued one at a time between the first
+    // MFMAs of unit u (its buffer was last read in unit u-1, which every wave left before the barrier
+    // inside unit u-1); the fragments of k-step t+1 are read while k-step t is computed; the barrier
+    // that opens unit u+1 and the reads of its first fragments sit before the last half k-step.
+    constexpr int NM = WM * WN;               // MFMAs per k-step
+    constexpr int DIST = C::NUNIT - 1;
     int buf = 0;
-    for (int s = 0; s < nstage; ++s) {
-        const uint8_t* st = lds + buf * C::STAGE_BYTES;
-        const int buf1 = buf == 2 ? 0 : buf + 1, buf2 = buf == 0 ? 2 : buf - 1;
-        const int fetch = min(s + 2, nstage - 1);
-        read_codes(1, st);
+    auto run_unit = [&](int u, auto nsteps_tag) {
+        constexpr int NSTEPS = decltype(nsteps_tag)::value;
+        constexpr int LAST_Q = NSTEPS * NM - NM / 2;
+        const uint8_t* st = lds + buf * C::UNIT_BYTES;
+        const int buf1 = buf + 1 == C::NUNIT ? 0 : buf + 1, bufd = buf == 0 ? C::NUNIT - 1 : buf - 1;
+        const int fetch = min(u + DIST, nunit - 1);
 #pragma unroll
-        for (int d = 0; d < C::NDMA / 2; ++d) issue_one(d, fetch, buf2);
-        mfmas(0, 0, WM * WN);
+        for (int t = 0; t < NSTEPS; ++t) {
+            if (t + 1 < NSTEPS) {
+                read_codes((t + 1) & 1, t + 1, st);
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
-        for (int d = C::NDMA / 2; d < C::NDMA; ++d) issue_one(d, fetch, buf2);
-        mfmas(1, 0, HALF);
-        // stage s+1 must have landed: this stage's own copies are younger
-        wait_vmcnt<C::NDMA>();
-        wg_barrier();
-        read_codes(0, lds + buf1 * C::STAGE_BYTES);
-        read_scales(lds + buf1 * C::STAGE_BYTES, sa_n, sw_n);
-        mfmas(1, HALF, WM * WN - HALF);
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j) {
+                    const int q = t * NM + i * WN + j;
+                    if (q == LAST_Q) {
+                        // unit u+1 must have landed: the copies of the DIST - 1 later units are younger
+                        wait_vmcnt<(DIST - 1) * C::NDMA>();
+                        wg_barrier();
+                        read_codes(0, 0, lds + buf1 * C::UNIT_BYTES);
+                        read_scales(lds + buf1 * C::UNIT_BYTES, sa_n, sw_n);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    // weights as the row operand: see store_tile_swapped
+                    acc[i][j] = mfma_mx(fw[t & 1][j], fa[t & 1][i], acc[i][j], (int)(t < 2 ? sw[j].x : sw[j].y),
+                                        (int)(t < 2 ? sa[i].x : sa[i].y), t & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (NSTEPS == 4 && q < C::NDMA) {
+                        issue_one(q, fetch, bufd);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+        }
 #pragma unroll
         for (int i = 0; i < WM; ++i) sa[i] = sa_n[i];
 #pragma unroll
         for (int j = 0; j < WN; ++j) sw[j] = sw_n[j];
         buf = buf1;
-    }
+    };
+    static_assert(C::NDMA <= 3 * NM, "copies are issued during the first three k-steps of a unit");
+
+#pragma unroll
+    for (int u = 0; u < DIST; ++u)
+#pragma unroll
+        for (int d = 0; d < C::NDMA; ++d) issue_one(d, min(u, nunit - 1), u);
+    wait_vmcnt<(DIST - 1) * C::NDMA>();
+    wg_barrier();
+    read_codes(0, 0, lds);
+    read_scales(lds, sa, sw);
+    const int nfull = nb >> 3;
+    for (int u = 0; u < nfull; ++u) run_unit(u, std::integral_constant<int, 4>{});
+    if (has_half) run_unit(nfull, std::integral_constant<int, 2>{});
     wait_vmcnt<0>();                            // no copy may still be in flight when the LDS is released
 
     const int m0 = wg_m0 + wrow0, n0 = wg_n0 + wcol0;
@@ -236,7 +278,7 @@ __global__ __launch_bounds__(256) void mx_gemm_direct_kernel(
 
 template <int WM, int WN, int GM, int GN, typename OutT>
 arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
-                             const uint8_t* w_scales, int M, int N, int nstage, OutT* y, int64_t ldy, hipStream_t stream) {
+                             const uint8_t* w_scales, int M, int N, int nb, OutT* y, int64_t ldy, hipStream_t stream) {
     using C = MxCfg<WM, WN, GM, GN>;
     auto kern = mx_gemm_staged_kernel<WM, WN, GM, GN, OutT>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -244,7 +286,7 @@ arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, co
     if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
     const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales, w_codes,
-                       w_scales, M, N, nstage, y, ldy, tiles_m, tiles_n);
+                       w_scales, M, N, nb, y, ldy, tiles_m, tiles_n);
     return check_launch("mx_gemm_staged_kernel");
 }
 
@@ -257,14 +299,13 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
                            ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 3) == 0;
     if ((nb & 3) == 0 && offsets_fit && aligned16) {
-        const int nstage = nb >> 2;
         const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
         if (t256 >= 256)
-            return launch_mx_staged<4, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nstage, y, ldy, stream);
+            return launch_mx_staged<4, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
         const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
         if (t128x256 >= 192)
-            return launch_mx_staged<2, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nstage, y, ldy, stream);
-        return launch_mx_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nstage, y, ldy, stream);
+            return launch_mx_staged<2, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
+        return launch_mx_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
     }
     dim3 grid((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128));
     hipLaunchKernelGGL(mx_gemm_direct_kernel<OutT>, grid, dim3(256), 0, stream, a_codes, a_scales, w_codes, w_scales,
