@@ -10,6 +10,9 @@ Weight Quantization").  The default workload is the LLaMA-3-8B q_proj prefill sh
 The timed region holds exactly --steps steps and nothing else on the stream; the same steps are
 then repeated with an event after every launch, which gives the per-kernel launch durations the
 rooflines use (those events cost a few microseconds per step, so they stay out of the timed region).
+`detail.rmsnorm_quant_ms` (the quantizer with RMSNorm fused in front) and `detail.mxfp4` (the same step
+in the MXFP4 variant of the format, whose GEMM runs on the scaled FP4 matrix instruction) are reported
+beside the headline figures and do not enter `value`.
 
 Prints ONE JSON line.  `value` = 2*M*N*K' / step time, in TFLOP/s.  `roofline` prices the dominant
 kernel (the GEMM; fp16 MFMA peak because operands are decoded exactly to fp16).  `cpu_baseline`
@@ -29,6 +32,7 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_MFMA_F16_TFLOPS = 2500.0  # MI355X dense fp16/bf16 MFMA
+PEAK_MFMA_FP4_TFLOPS = 10100.0 # MI355X dense fp4 MFMA (the MXFP4 variant's GEMM)
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (see
 # profiles/), scaled by the factor the same counters read for a plain copy of known size.
@@ -123,6 +127,33 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
         e1.record()
     torch.cuda.synchronize()
     out["rmsnorm_quant_ms"] = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / n
+    # the MXFP4 variant of the same step (block 32, E8M0 scales; the GEMM runs on the scaled FP4 matrix
+    # instruction): its own figures, not part of `value`
+    if wl.K % 32 == 0 and S % 32 == 0:
+        mwc, mwsc = B.arcq_mx_pack_weight(W, perm, S)
+        mac = torch.empty((wl.M, Kp // 2), dtype=torch.uint8, device="cuda")
+        masc = torch.empty((wl.M, Kp // 32), dtype=torch.uint8, device="cuda")
+
+        def mx_step():
+            B.arcq_mx_quantize_act(X, perm, S, codes=mac, scales=masc)
+            B.arcq_mx_gemm(mac, masc, mwc, mwsc, y=Y)
+        for _ in range(3):
+            mx_step()
+        torch.cuda.synchronize()
+        n = max(3, min(steps, 20))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            mx_step()
+        e1.record()
+        torch.cuda.synchronize()
+        out["mx_step_ms"] = e0.elapsed_time(e1) / n
+        e0.record()
+        for _ in range(n):
+            B.arcq_mx_gemm(mac, masc, mwc, mwsc, y=Y)
+        e1.record()
+        torch.cuda.synchronize()
+        out["mx_gemm_ms"] = e0.elapsed_time(e1) / n
     if vendor_ref:
         # context only: the vendor library's bf16 GEMM (hipBLASLt through torch.matmul) on the
         # unquantized operands, K columns (no augmentation); not part of the product path
@@ -159,6 +190,11 @@ def summarize(wl, S, t):
         "rmsnorm_quant_ms": round(t["rmsnorm_quant_ms"], 5),
         "rmsnorm_quant_gbs": round((qb + 2 * wl.K) / t["rmsnorm_quant_ms"] / 1e6, 1),
     }
+    if "mx_step_ms" in t:
+        s["mxfp4"] = {"step_ms": round(t["mx_step_ms"], 5), "gemm_ms": round(t["mx_gemm_ms"], 5),
+                      "step_tflops": round(fl / t["mx_step_ms"] / 1e9, 2),
+                      "gemm_tflops": round(fl / t["mx_gemm_ms"] / 1e9, 2),
+                      "gemm_frac_of_fp4_mfma_peak": round(fl / t["mx_gemm_ms"] / 1e9 / PEAK_MFMA_FP4_TFLOPS, 4)}
     if "vendor_bf16_gemm_ms" in t:
         s["vendor_bf16_gemm_ms"] = round(t["vendor_bf16_gemm_ms"], 5)
         s["linear_vs_vendor_bf16"] = round(t["vendor_bf16_gemm_ms"] / t["dev_ms"], 3)   # > 1: quantized linear is faster
