@@ -21,7 +21,7 @@ def test_algorithmic_byte_and_flop_counts():
     assert abs(bench.gemm_flops(8192, 8192, 29696) - 3.9857e12) < 1e9
     assert bench.gemm_bytes(16, 4096, 14592) == (16 + 4096) * (7296 + 912) + 16 * 4096 * 2
     for wl, d in bench.MEASURED_TRAFFIC.items():
-        assert set(d) == {"arcq_gemm", "arcq_quantize_act", "arcq_rmsnorm_quantize_act"} and all(v > 0 for v in d.values())
+        assert {"arcq_gemm", "arcq_quantize_act"} <= set(d) and all(v > 0 for v in d.values())
 
 
 def test_profiles_name_their_commands():
