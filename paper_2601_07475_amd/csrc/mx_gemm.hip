@@ -276,6 +276,110 @@ __global__ __launch_bounds__(256) void mx_gemm_direct_kernel(
     store_tile_swapped<2, 2>(acc, m0, n0, r, h, M, N, 1.0f, y, ldy, false);
 }
 
+// Weight-streaming kernel for M <= 128 (decode, batched decode, short prefill) and K' % 128 == 0: bound by
+// reading the packed weights once (17/32 byte per weight).  v_mfma_scale_f32_16x16x128_f8f6f4: lane
+// (i = lane % 16, q = lane / 16) supplies the 32 values of block 4c + q of row i for the 128-k chunk c,
+// with that block's scale byte.  A lane loads 16 bytes of codes per row and chunk (a wave: 16 rows x 64
+// contiguous bytes) and the 4 scale bytes of the chunk (the four lanes of a row load the same word and
+// each extracts its own byte).  MT tiles of 16 activation rows share every weight fragment; the WAVES
+// waves of a workgroup split K' and add their partial tiles through LDS.  Everything is loaded straight
+// into registers; latency is hidden by occupancy.
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+template <int MT, int NT, int WAVES, int U, typename OutT>
+__global__ __launch_bounds__(WAVES * 64) void mx_gemm_skinny_kernel(
+    const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
+    const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N, int nb,
+    OutT* __restrict__ y, int64_t ldy) {
+    __shared__ float red[WAVES][MT * NT][4][64];
+    static_assert(sizeof(float) * WAVES * MT * NT * 256 <= 64 * 1024, "partial tiles must fit the static LDS limit");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, q = lane >> 4;
+    const int n0 = blockIdx.x * (16 * NT);
+    const int64_t cpitch = (int64_t)nb * 16, spitch = nb;
+    const int nchunk = nb >> 2;                                  // nb % 4 == 0 on this path
+
+    const uint8_t *ac[MT], *as[MT];
+#pragma unroll
+    for (int r = 0; r < MT; ++r) {
+        const int m = min(16 * r + i, M - 1);                    // rows past M repeat row M-1 and are not stored
+        ac[r] = a_codes + (int64_t)m * cpitch + 16 * q;
+        as[r] = a_scales + (int64_t)m * spitch;
+    }
+    const uint8_t *wc[NT], *ws[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int n = min(n0 + 16 * t + i, N - 1);
+        wc[t] = w_codes + n * cpitch + 16 * q;
+        ws[t] = w_scales + n * spitch;
+    }
+    float4v acc[MT][NT];
+#pragma unroll
+    for (int r = 0; r < MT; ++r)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[r][t] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    for (int c0 = wave * U; c0 < nchunk; c0 += WAVES * U) {
+        uint4 ca[U][MT], cw[U][NT];
+        uint32_t sa[U][MT], sw[U][NT];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            // chunks past the end re-read the last one and count as zero (codes zeroed, scale byte of 1.0)
+            const bool ok = c0 + u < nchunk;
+            const int64_t c = ok ? c0 + u : nchunk - 1;
+#pragma unroll
+            for (int r = 0; r < MT; ++r) {
+                ca[u][r] = *reinterpret_cast<const uint4*>(ac[r] + 64 * c);
+                sa[u][r] = *reinterpret_cast<const uint32_t*>(as[r] + 4 * c);
+                if (!ok) { ca[u][r] = make_uint4(0, 0, 0, 0); sa[u][r] = 0x7F7F7F7Fu; }
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                cw[u][t] = *reinterpret_cast<const uint4*>(wc[t] + 64 * c);
+                sw[u][t] = *reinterpret_cast<const uint32_t*>(ws[t] + 4 * c);
+                if (!ok) { cw[u][t] = make_uint4(0, 0, 0, 0); sw[u][t] = 0x7F7F7F7Fu; }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int8v vw = {(int)cw[u][t].x, (int)cw[u][t].y, (int)cw[u][t].z, (int)cw[u][t].w, 0, 0, 0, 0};
+                const int bw = (int)((sw[u][t] >> (8 * q)) & 0xFFu);
+#pragma unroll
+                for (int r = 0; r < MT; ++r) {
+                    const int8v va = {(int)ca[u][r].x, (int)ca[u][r].y, (int)ca[u][r].z, (int)ca[u][r].w, 0, 0, 0, 0};
+                    const int ba = (int)((sa[u][r] >> (8 * q)) & 0xFFu);
+                    // activations as the 16-row operand: lane holds column n = lane % 16, register e row 4 (lane / 16) + e
+                    acc[r][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(va, vw, acc[r][t], 4, 4, 0, ba, 0, bw);
+                }
+            }
+    }
+#pragma unroll
+    for (int r = 0; r < MT; ++r)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) red[wave][r * NT + t][e][lane] = acc[r][t][e];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < MT * NT * 4 * 64; idx += WAVES * 64) {
+        const int rt = idx >> 8, e = (idx >> 6) & 3, l = idx & 63;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) sum += red[w][rt][e][l];
+        const int m = 16 * (rt / NT) + 4 * (l >> 4) + e, n = n0 + 16 * (rt % NT) + (l & 15);
+        if (m < M && n < N) store_out(y + (int64_t)m * ldy + n, sum);
+    }
+}
+
+template <int MT, int NT, int WAVES, int U, typename OutT>
+arcq_status launch_mx_skinny(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                             const uint8_t* w_scales, int M, int N, int nb, OutT* y, int64_t ldy, hipStream_t stream) {
+    hipLaunchKernelGGL((mx_gemm_skinny_kernel<MT, NT, WAVES, U, OutT>), dim3((N + 16 * NT - 1) / (16 * NT)),
+                       dim3(WAVES * 64), 0, stream, a_codes, a_scales, w_codes, w_scales, M, N, nb, y, ldy);
+    return check_launch("mx_gemm_skinny_kernel");
+}
+
 template <int WM, int WN, int GM, int GN, typename OutT>
 arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                              const uint8_t* w_scales, int M, int N, int nb, OutT* y, int64_t ldy, hipStream_t stream) {
@@ -298,6 +402,27 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
     const bool offsets_fit = (uint64_t)M * (uint64_t)nb * 16 < 0xFFFF0000ull && (uint64_t)N * (uint64_t)nb * 16 < 0xFFFF0000ull;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
                            ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 3) == 0;
+    if (M <= 128 && (nb & 3) == 0 && aligned16) {
+        const int64_t tiles = (N + 15) / 16;
+#define ARCQ_MX_SKINNY(MT_, NT_, W_, U_) \
+    return launch_mx_skinny<MT_, NT_, W_, U_>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream)
+        if (M <= 16) {
+            if (tiles >= 800) ARCQ_MX_SKINNY(1, 4, 8, 1);
+            if (tiles >= 400) ARCQ_MX_SKINNY(1, 2, 8, 2);
+            ARCQ_MX_SKINNY(1, 1, 8, 2);
+        }
+        if (M <= 32) {
+            if (tiles >= 800) ARCQ_MX_SKINNY(2, 2, 8, 1);
+            ARCQ_MX_SKINNY(2, 1, 8, 2);
+        }
+        if (M <= 64) {
+            if (tiles >= 800) ARCQ_MX_SKINNY(4, 2, 8, 1);
+            ARCQ_MX_SKINNY(4, 1, 8, 1);
+        }
+        if (tiles >= 800) ARCQ_MX_SKINNY(8, 2, 4, 1);
+        ARCQ_MX_SKINNY(8, 1, 8, 1);
+#undef ARCQ_MX_SKINNY
+    }
     if ((nb & 3) == 0 && offsets_fit && aligned16) {
         const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
         if (t256 >= 256)

@@ -502,6 +502,9 @@ def test_mx_quantize_every_fp16_value():
 MX_GEMM_SHAPES = [  # M, N, K, S: fallback kernel (K' % 128 != 0), every staged tile configuration, ragged edges
     (1, 1, 32, 0), (77, 200, 64, 32), (130, 129, 96, 32), (16, 512, 512, 0), (128, 256, 256, 0), (257, 131, 1024, 0),
     (300, 77, 2048, 2048), (500, 260, 4096, 128), (16, 1000, 4096, 256), (1990, 4070, 256, 128), (4000, 4100, 96, 32),
+    # weight-streaming kernel: 1, 2, 4, 8 tiles of 16 rows, ragged N, one chunk, many chunks split over the waves
+    (8, 40, 128, 0), (20, 300, 512, 128), (33, 77, 2048, 2048), (64, 4097, 256, 128), (100, 260, 4096, 128),
+    (17, 14336, 512, 512), (48, 2048, 4096, 1024), (1, 4096, 14336, 256),
 ]
 
 
