@@ -64,7 +64,8 @@ __device__ __forceinline__ void mx_residual_block32(const float (&v)[32], float 
 
 // BPT  32-channel blocks per lane (1 or 2);  MODE 0: activations (residual blocks), 1: weights (copies)
 // DB   two LDS row buffers (rows up to 36864 channels), else one.
-template <int BPT, int MODE, bool DB>
+// STREAM  inputs far larger than the caches: rows are loaded with the non-temporal, system-scope policy.
+template <int BPT, int MODE, bool DB, bool STREAM>
 __global__ __launch_bounds__(1024) void mx_quantize_rows_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int rows, int K, int S, const int32_t* __restrict__ perm,
     uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(1024) void mx_quantize_rows_kernel(
 #pragma unroll
         for (int p = 0; p < NPRE; ++p) {
             const uint32_t dst = base + 16u * (wave_first + (uint32_t)(p * T));
-            __builtin_amdgcn_global_load_lds((global_void_t*)(src + piece[p]), (lds_void_t*)(lds_row + dst), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((global_void_t*)(src + piece[p]), (lds_void_t*)(lds_row + dst), 16, 0, STREAM ? 18 : 0);   // 2 = nt, 16 = sc1
         }
     };
 
@@ -158,10 +159,10 @@ __global__ __launch_bounds__(1024) void mx_quantize_rows_kernel(
     }
 }
 
-template <int BPT, int MODE, bool DB>
+template <int BPT, int MODE, bool DB, bool STREAM>
 arcq_status launch_mx_t(int threads, size_t lds, const void* x, int64_t rows, int64_t K, int64_t ldx,
                         const int32_t* perm, int64_t S, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
-    auto kern = mx_quantize_rows_kernel<BPT, MODE, DB>;
+    auto kern = mx_quantize_rows_kernel<BPT, MODE, DB, STREAM>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -200,15 +201,19 @@ arcq_status launch_mx_quantize(int mode, const void* x, int64_t rows, int64_t K,
     const size_t stride = (size_t)64 * bpt * threads;
     const bool db = 2 * stride <= 144 * 1024;
     const size_t lds = db ? 2 * stride : stride;
+    const bool stream_in = (uint64_t)rows * (uint64_t)K * 2 > (192ull << 20);   // beyond what the caches can hold
+#define ARCQ_MX_CASE2(B, D, ST) \
+    return mode == 0 ? launch_mx_t<B, 0, D, ST>(threads, lds, x, rows, K, ldx, perm, S, codes, scales, stream) \
+                     : launch_mx_t<B, 1, D, ST>(threads, lds, x, rows, K, ldx, perm, S, codes, scales, stream)
 #define ARCQ_MX_CASE(B, D) \
-    return mode == 0 ? launch_mx_t<B, 0, D>(threads, lds, x, rows, K, ldx, perm, S, codes, scales, stream) \
-                     : launch_mx_t<B, 1, D>(threads, lds, x, rows, K, ldx, perm, S, codes, scales, stream)
+    if (stream_in) { ARCQ_MX_CASE2(B, D, true); } else { ARCQ_MX_CASE2(B, D, false); }
     if (db) {
-        if (bpt == 1) ARCQ_MX_CASE(1, true);
+        if (bpt == 1) { ARCQ_MX_CASE(1, true); }
         ARCQ_MX_CASE(2, true);
     }
     ARCQ_MX_CASE(2, false);
 #undef ARCQ_MX_CASE
+#undef ARCQ_MX_CASE2
 }
 
 }  // namespace arcq
