@@ -18,7 +18,10 @@ Prints ONE JSON line.  `value` = 2*M*N*K' / step time, in TFLOP/s.  `roofline` p
 kernel (the GEMM; fp16 MFMA peak because operands are decoded exactly to fp16).  `cpu_baseline`
 is the numpy oracle timed on the host cores on the same workload.  `also` holds the other
 single-GPU workloads (fewer steps): the HBM-streaming claim of the quantizer is made on
-c5_llama70b_down, the decode shapes c3a/c3b are weight-streaming bound.
+c5_llama70b_down, the decode shapes c3a/c3b are weight-streaming bound (their `gemm_rotating_ms` cycles
+over enough weight copies to exceed the last-level cache, so every launch streams its weight from HBM).
+`s_sweep` times quantizer and GEMM against S at the main workload's shape (Section 3.4: cost linear in
+S/K); `machine.device_copy_gbs` is the plain copy rate of the box the run was on.
 """
 import argparse
 import json
@@ -154,6 +157,27 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
         e1.record()
         torch.cuda.synchronize()
         out["mx_gemm_ms"] = e0.elapsed_time(e1) / n
+    if wl.M <= 128:
+        # decode shapes: the packed weight (tens of MB) stays in the 256 MB last-level cache between
+        # launches above; rotating over enough copies to exceed it gives the figure with the weight
+        # streamed from HBM on every launch, which is what a model with many layers sees
+        wbytes = wc.numel() + wsc.numel()
+        ncopy = max(2, -(-384 * 2**20 // wbytes))
+        copies = [(wc.clone(), wsc.clone()) for _ in range(ncopy)]
+        gemms = [B.prepare_gemm(ac, asc, sTx, c, sc, sTw, Y, ws) for c, sc in copies]
+        for g in gemms:
+            g()
+        torch.cuda.synchronize()
+        n = 2 * ncopy
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            gemms[i % ncopy]()
+        e1.record()
+        torch.cuda.synchronize()
+        out["gemm_rotating_ms"] = e0.elapsed_time(e1) / n
+        out["gemm_rotating_copies"] = ncopy
+        del copies, gemms
     if vendor_ref:
         # context only: the vendor library's bf16 GEMM (hipBLASLt through torch.matmul) on the
         # unquantized operands, K columns (no augmentation); not part of the product path
@@ -198,8 +222,71 @@ def summarize(wl, S, t):
     if "vendor_bf16_gemm_ms" in t:
         s["vendor_bf16_gemm_ms"] = round(t["vendor_bf16_gemm_ms"], 5)
         s["linear_vs_vendor_bf16"] = round(t["vendor_bf16_gemm_ms"] / t["dev_ms"], 3)   # > 1: quantized linear is faster
+    if "gemm_rotating_ms" in t:
+        s["gemm_rotating_ms"] = round(t["gemm_rotating_ms"], 5)
+        s["gemm_rotating_copies"] = t["gemm_rotating_copies"]
+        s["gemm_rotating_gbs"] = round(gb / t["gemm_rotating_ms"] / 1e6, 1)
+        s["gemm_rotating_frac_of_hbm_peak"] = round(gb / t["gemm_rotating_ms"] / 1e6 / PEAK_HBM_GBS, 4)
     s["traffic_bytes"] = MEASURED_TRAFFIC.get(wl.name)
     return s
+
+
+def s_sweep(torch, B, case, values, iters=20):
+    """GEMM and quantizer time against the number S of augmented channels at the workload's shape
+    (Section 3.4: the cost of compensation is the extra S/K of the reduction dimension, so the GEMM
+    time should rise linearly in S from the S = 0 point, which is plain NVFP4 W4A4)."""
+    import numpy as np
+    wl = case["wl"]
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    X, W, perm = d(case["X"]), d(case["W"]), d(case["perm"])
+    sTx, sTw = float(case["sT_x"]), float(case["sT_w"])
+    Y = torch.empty((wl.M, wl.N), dtype=torch.float16, device="cuda")
+    rows = []
+    for S in values:
+        if S > wl.K:
+            continue
+        Kp = wl.K + S
+        wc, wsc = B.arcq_pack_weight(W, perm, S, sTw)
+        ac = torch.empty((wl.M, Kp // 2), dtype=torch.uint8, device="cuda")
+        asc = torch.empty((wl.M, Kp // 16), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(max(B.arcq_gemm_workspace_size(wl.M, wl.N, Kp), 1), dtype=torch.uint8, device="cuda")
+        quant = B.prepare_quantize_act(X, perm, S, sTx, ac, asc)
+        gemm = B.prepare_gemm(ac, asc, sTx, wc, wsc, sTw, Y, ws)
+        for _ in range(3):
+            quant()
+            gemm()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record()
+        for _ in range(iters):
+            quant()
+        ev[1].record()
+        for _ in range(iters):
+            gemm()
+        ev[2].record()
+        torch.cuda.synchronize()
+        rows.append({"S": S, "quant_ms": round(ev[0].elapsed_time(ev[1]) / iters, 5),
+                     "gemm_ms": round(ev[1].elapsed_time(ev[2]) / iters, 5)})
+    g0 = rows[0]["gemm_ms"] if rows and rows[0]["S"] == 0 else None
+    for r in rows:
+        r["gemm_vs_S0"] = round(r["gemm_ms"] / g0, 4) if g0 else None
+        r["Kp_vs_K"] = round((wl.K + r["S"]) / wl.K, 4)
+    return rows
+
+
+def copy_rate(torch, nbytes=1 << 30, iters=5):
+    """Plain device-to-device copy of 1 GiB: the streaming rate this machine reaches (read + write bytes per second)."""
+    src = torch.ones(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    return round(2 * nbytes * iters / e0.elapsed_time(e1) / 1e6, 1)
 
 
 def cpu_baseline(case):
@@ -243,6 +330,8 @@ def main():
                     help="comma-separated extra workloads reported under 'also' (fewer steps); '' for none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-vendor-ref", action="store_true")
+    ap.add_argument("--s-sweep", default="0,128,256,512,1024,2048",
+                    help="values of S timed at the main workload's shape, reported under 's_sweep'; '' for none")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run three plain 1 GiB device copies (a kernel of known traffic, for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc pass)")
@@ -286,6 +375,9 @@ def main():
         del c2
         torch.cuda.empty_cache()
 
+    sweep = s_sweep(torch, B, case, [int(v) for v in args.s_sweep.split(",") if v]) if args.s_sweep else None
+    stream_gbs = copy_rate(torch)
+
     traffic = MEASURED_TRAFFIC.get(args.workload, {})
     out = {
         "metric": "augmented NVFP4 GEMM TFLOPS (2*M*N*K') over the quantizer+GEMM step; quantizer GB/s and % of MI355X roofline alongside",
@@ -304,7 +396,8 @@ def main():
                                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": s["quant_frac_of_hbm_peak"],
                                "traffic": traffic.get("arcq_quantize_act"),
                                "note": "this workload (22 MB) is cache-resident: effective GB/s; the HBM-streaming figure is also.c5_llama70b_down.quant_gbs"},
-        "detail": s, "also": also,
+        "detail": s, "also": also, "s_sweep": sweep,
+        "machine": {"device_copy_gbs": stream_gbs, "note": "1 GiB device-to-device copy, read + write bytes"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case)

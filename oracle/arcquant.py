@@ -26,6 +26,15 @@ Packed layout (Section 3.2 step (3): plain concatenation along K):
   codes  uint8 [rows, K'/2]  byte i = element 2i in bits 0-3, element 2i+1 in bits 4-7
   scales uint8 [rows, K'/16] block b < K/16 primary; block K/16 + i is the residual
                              of primary block (K - S)/16 + i
+
+Two variants, both off by default:
+  layout="interleaved"   Appendix D "Interleaved Channel Layout": the same blocks in another physical
+                         order -- the (K - S)/16 blocks without compensation first, then every outlier
+                         block immediately followed by its residual block (by its copy, for weights);
+  scale_rounding="up"    the block scale is the smallest E4M3 value not below u instead of the nearest
+                         (Section 3.4 takes alpha = s / (max / q_max) in [1, 1.125], a scale never
+                         rounded down); u > 448 still saturates, and a nonzero u below the smallest
+                         subnormal 2^-9 goes to 2^-9 rather than to 0.
 """
 import numpy as np
 
@@ -45,7 +54,35 @@ def tensor_ginv(s_T):
     return _f32(1.0) / (_f32(QMAX) * s_T)
 
 
-def quantize_blocks(v, s_T):
+def _scale_encoder(scale_rounding):
+    if scale_rounding == "nearest":
+        return F.e4m3_encode_rne_sat
+    if scale_rounding == "up":
+        return F.e4m3_encode_up_sat
+    raise ValueError("scale_rounding must be 'nearest' or 'up'")
+
+
+def interleaved_order(K, S):
+    """Appendix D: physical block position -> block index in the concatenated layout."""
+    nb, no = K // G, S // G
+    order = list(range(nb - no))
+    for i in range(no):
+        order.append(nb - no + i)        # primary block of outlier group i
+        order.append(nb + i)             # its residual (or, for weights, its copy)
+    return np.array(order, dtype=np.int64)
+
+
+def _lay_out(codes, sb, K, S, layout):
+    """codes [rows, K'/16, 16], sb [rows, K'/16] in concatenated order -> the requested order."""
+    if layout == "concat":
+        return codes, sb
+    if layout == "interleaved":
+        order = interleaved_order(K, S)
+        return codes[:, order], sb[:, order]
+    raise ValueError("layout must be 'concat' or 'interleaved'")
+
+
+def quantize_blocks(v, s_T, scale_rounding="nearest"):
     """NVFP4-quantize blocks of 16 (Section 3.1 eq. (1), Appendix A).
 
     v    float32 [..., 16], finite
@@ -63,7 +100,7 @@ def quantize_blocks(v, s_T):
     absv = np.abs(v)
     amax = absv.max(axis=-1)                                   # exact
     u = (amax * ginv).astype(np.float32)                       # one fp32 rounding
-    sbyte = F.e4m3_encode_rne_sat(u)
+    sbyte = _scale_encoder(scale_rounding)(u)
     s = (F.e4m3_decode(sbyte).astype(np.float32) * s_T).astype(np.float32)
 
     nz = s != 0
@@ -108,7 +145,7 @@ def _check_shape(K, S):
         raise ValueError("need K > 0, K % 16 == 0, 0 <= S <= K, S % 16 == 0")
 
 
-def quantize_act(X, perm, S, s_T):
+def quantize_act(X, perm, S, s_T, layout="concat", scale_rounding="nearest"):
     """Online activation quantizer (Section 3.2 "Online Activation Quantization").
 
     (1) reorder channels: Xp[:, j] = X[:, perm[j]]; quantize every block of 16;
@@ -124,13 +161,14 @@ def quantize_act(X, perm, S, s_T):
     assert perm.shape == (K,)
     Xp = X[:, perm].astype(np.float32).reshape(M, K // G, G)
 
-    sb, codes, s = quantize_blocks(Xp, s_T)
+    sb, codes, s = quantize_blocks(Xp, s_T, scale_rounding)
     if S:
         o = (K - S) // G
         r = residual_blocks(Xp[:, o:], codes[:, o:], s[:, o:])
-        sb_r, codes_r, _ = quantize_blocks(r, s_T)
+        sb_r, codes_r, _ = quantize_blocks(r, s_T, scale_rounding)
         codes = np.concatenate([codes, codes_r], axis=1)
         sb = np.concatenate([sb, sb_r], axis=1)
+    codes, sb = _lay_out(codes, sb, K, S, layout)
     Kp = K + S
     return pack_nibbles(codes.reshape(M, Kp)), sb.reshape(M, Kp // G)
 
@@ -172,12 +210,12 @@ def rmsnorm(X, gamma, eps):
     return (t.astype(np.float32) * gamma.astype(np.float32)[None, :]).astype(np.float16)
 
 
-def rmsnorm_quantize_act(X, gamma, eps, perm, S, s_T):
+def rmsnorm_quantize_act(X, gamma, eps, perm, S, s_T, layout="concat", scale_rounding="nearest"):
     """The fused kernel of Section 3.3: RMSNorm, then the online activation quantizer."""
-    return quantize_act(rmsnorm(X, gamma, eps), perm, S, s_T)
+    return quantize_act(rmsnorm(X, gamma, eps), perm, S, s_T, layout, scale_rounding)
 
 
-def pack_weight(W, perm, S, s_T):
+def pack_weight(W, perm, S, s_T, layout="concat", scale_rounding="nearest"):
     """Offline weight packer (Section 3.2 "Offline Weight Quantization").
 
     Reorder the K axis to match X, quantize (plain round-to-nearest), then append
@@ -189,11 +227,12 @@ def pack_weight(W, perm, S, s_T):
     N, K = W.shape
     _check_shape(K, S)
     Wp = W[:, np.asarray(perm)].astype(np.float32).reshape(N, K // G, G)
-    sb, codes, _ = quantize_blocks(Wp, s_T)
+    sb, codes, _ = quantize_blocks(Wp, s_T, scale_rounding)
     if S:
         o = (K - S) // G
         codes = np.concatenate([codes, codes[:, o:]], axis=1)
         sb = np.concatenate([sb, sb[:, o:]], axis=1)
+    codes, sb = _lay_out(codes, sb, K, S, layout)
     Kp = K + S
     return pack_nibbles(codes.reshape(N, Kp)), sb.reshape(N, Kp // G)
 

@@ -47,6 +47,16 @@ def e4m3_nearest_sat(u):
     return _nearest_even(Fr(u), _E4M3_POS)
 
 
+def e4m3_up_sat(u):
+    """Byte of the smallest E4M3 value >= u (a loop over all 127 values); beyond 448: 448."""
+    u = Fr(u)
+    best = None
+    for byte, val in _E4M3_POS:
+        if val >= u and (best is None or val < best[1]):
+            best = (byte, val)
+    return 0x7E if best is None else best[0]
+
+
 def round_f32(q):
     """Round a rational to the nearest IEEE binary32 value (ties to even), as a Fraction.
     Subnormals are kept; overflow is not handled (never reached by the tests)."""
@@ -134,17 +144,18 @@ def rmsnorm_row(x, gamma, eps):
     return out
 
 
-def quantize_block(v, s_T):
+def quantize_block(v, s_T, scale_up=False):
     """v: 16 numbers exactly representable in fp32 (floats or Fractions), s_T fp32-valued.
     Returns (scale_byte, [16 codes], [16 residuals as Fractions]).
-    Same recipe as oracle.arcquant's header, every fp32 rounding done by round_f32."""
+    Same recipe as oracle.arcquant's header, every fp32 rounding done by round_f32;
+    scale_up: the block scale is rounded up instead of to nearest."""
     v = [Fr(x) for x in v]
     neg = [(x < 0) for x in v]
     s_T = Fr(s_T)
     ginv = round_f32(1 / round_f32(6 * s_T))
     amax = max(abs(x) for x in v)
     u = round_f32(amax * ginv)
-    sb = e4m3_nearest_sat(u)
+    sb = e4m3_up_sat(u) if scale_up else e4m3_nearest_sat(u)
     s = round_f32(e4m3_value(sb) * s_T)
     codes, res = [], []
     for x, n in zip(v, neg):

@@ -92,3 +92,14 @@ def e4m3_encode_rne_sat(u):
     out = np.where(take_hi, hi, lo)
     out = np.where(u >= 448.0, 0x7E, out)
     return out.astype(np.uint8)
+
+
+def e4m3_encode_up_sat(u):
+    """Byte (0x00..0x7E) of the smallest finite E4M3 value that is not below u >= 0 (rounding up);
+    u above 448 saturates to 448.  The error analysis of Section 3.4 takes the ratio alpha of the
+    stored scale to the ideal one in [1, 1.125]: a scale that is never rounded down."""
+    u = np.asarray(u, dtype=np.float64)
+    if np.any(~(u >= 0)):
+        raise ValueError("e4m3_encode_up_sat expects finite u >= 0")
+    hi = np.searchsorted(E4M3_POS, u, side="left")       # first entry >= u
+    return np.minimum(hi, len(E4M3_POS) - 1).astype(np.uint8)
