@@ -52,6 +52,10 @@ typedef int arcq_status;
 #define ARCQ_DTYPE_F16 0
 #define ARCQ_DTYPE_F32 1
 
+/* flags of the *_ex entry points (0 = the behaviour of the plain entry points) */
+#define ARCQ_LAYOUT_INTERLEAVED 1u   /* Appendix D "Interleaved Channel Layout" */
+#define ARCQ_SCALE_ROUND_UP     2u   /* block scale never below max/q_max: alpha >= 1 of Section 3.4 */
+
 /* Library version, major*10000 + minor*100 + patch. */
 int arcq_version(void);
 
@@ -108,6 +112,34 @@ arcq_status arcq_rmsnorm_quantize_act(const void* x, int64_t M, int64_t K, int64
 arcq_status arcq_pack_weight(const void* w, int64_t N, int64_t K, int64_t ldw,
                              const int32_t* perm, int64_t S, float tensor_scale,
                              uint8_t* codes, uint8_t* scales, void* stream);
+
+/*
+ * Variants of the three calls above, selected by `flags` (an OR of the ARCQ_LAYOUT_ / ARCQ_SCALE_ bits;
+ * any other bit is ARCQ_INVALID_ARG; flags = 0 is the plain call).  Everything else, sizes included, is
+ * unchanged.  Both operands of a GEMM must be packed with the same flags.
+ *
+ * ARCQ_LAYOUT_INTERLEAVED (Appendix D "Interleaved Channel Layout"): the same blocks in another physical
+ *   order along K'.  The (K-S)/16 blocks without compensation come first, in order; then every outlier
+ *   block is immediately followed by its partner (its quantized residual for activations, its verbatim
+ *   copy for weights): primary block (K-S)/16 + i sits at block position (K-S)/16 + 2i, its partner at
+ *   (K-S)/16 + 2i + 1, for codes and scale bytes alike.  arcq_gemm reduces over K' in any order, so the
+ *   product is the one of the plain layout up to the order of the fp32 sums.
+ * ARCQ_SCALE_ROUND_UP (Section 3.4 takes the ratio alpha of the stored block scale to max/q_max in
+ *   [1, 1.125]; Section 3.1 eq. (1) leaves the rounding open): the scale byte is the smallest E4M3 value
+ *   not below amax / (6 * tensor_scale) instead of the nearest one, for primary and residual blocks, so no
+ *   element saturates at 6; it still saturates at 448, and a nonzero quotient below the smallest subnormal
+ *   2^-9 gets 2^-9 rather than 0.
+ */
+arcq_status arcq_quantize_act_ex(const void* x, int64_t M, int64_t K, int64_t ldx,
+                                 const int32_t* perm, int64_t S, float tensor_scale, uint32_t flags,
+                                 uint8_t* codes, uint8_t* scales, void* stream);
+arcq_status arcq_rmsnorm_quantize_act_ex(const void* x, int64_t M, int64_t K, int64_t ldx,
+                                         const void* gamma, float eps,
+                                         const int32_t* perm, int64_t S, float tensor_scale, uint32_t flags,
+                                         uint8_t* codes, uint8_t* scales, void* stream);
+arcq_status arcq_pack_weight_ex(const void* w, int64_t N, int64_t K, int64_t ldw,
+                                const int32_t* perm, int64_t S, float tensor_scale, uint32_t flags,
+                                uint8_t* codes, uint8_t* scales, void* stream);
 
 /* Bytes of workspace arcq_gemm needs for this problem (may be 0).  Host arithmetic only. */
 arcq_status arcq_gemm_workspace_size(int64_t M, int64_t N, int64_t Kp, size_t* bytes);
@@ -196,6 +228,20 @@ arcq_status arcq_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
                          const uint8_t* w_codes, const uint8_t* w_scales,
                          int64_t M, int64_t N, int64_t Kp,
                          void* y, int y_dtype, int64_t ldy, void* stream);
+
+/*
+ * The same two variants for MXFP4 (flags as for arcq_quantize_act_ex, blocks of 32):
+ * ARCQ_LAYOUT_INTERLEAVED puts primary block (K-S)/32 + i at block position (K-S)/32 + 2i and its partner
+ * right behind it (Appendix D); ARCQ_SCALE_ROUND_UP takes the smallest power of two X with
+ * block maximum <= 6 X (one step above the floor rule exactly when the maximum's significand exceeds 1.5),
+ * so no element saturates (alpha >= 1, Section 3.4).
+ */
+arcq_status arcq_mx_quantize_act_ex(const void* x, int64_t M, int64_t K, int64_t ldx,
+                                    const int32_t* perm, int64_t S, uint32_t flags,
+                                    uint8_t* codes, uint8_t* scales, void* stream);
+arcq_status arcq_mx_pack_weight_ex(const void* w, int64_t N, int64_t K, int64_t ldw,
+                                   const int32_t* perm, int64_t S, uint32_t flags,
+                                   uint8_t* codes, uint8_t* scales, void* stream);
 
 #ifdef __cplusplus
 }

@@ -15,6 +15,13 @@ Readings: an all-zero block gets scale byte 127 (X = 1) and zero codes; S is a m
 
 Packed layout: codes uint8 [rows, K'/2] (element 2i in bits 0-3 of byte i), scales uint8 [rows, K'/32];
 block b < K/32 primary, block K/32 + i the residual of primary block (K - S)/32 + i.
+
+Two variants, both off by default, as for NVFP4:
+  layout="interleaved"   Appendix D: blocks without compensation first, then every outlier block
+                         immediately followed by its residual block (its copy, for weights);
+  scale_rounding="up"    X is the smallest power of two with max |v| <= 6 X, so that no element clips
+                         (the scale is never below the ideal max / q_max: alpha >= 1 in Section 3.4);
+                         one more than the rule above exactly when max |v| / 2^floor(log2 max |v|) > 1.5.
 """
 import numpy as np
 
@@ -32,8 +39,29 @@ def e8m0_decode(b):
     return np.where(b == 255, np.nan, out)
 
 
-def quantize_blocks(v):
-    """v float32 [..., 32] finite -> (sbyte uint8 [...], codes uint8 [..., 32], X float64 [...])."""
+def interleaved_order(K, S):
+    """Appendix D: physical block position -> block index in the concatenated layout."""
+    nb, no = K // G, S // G
+    order = list(range(nb - no))
+    for i in range(no):
+        order += [nb - no + i, nb + i]
+    return np.array(order, dtype=np.int64)
+
+
+def _lay_out(codes, sb, K, S, layout):
+    if layout == "concat":
+        return codes, sb
+    if layout == "interleaved":
+        order = interleaved_order(K, S)
+        return codes[:, order], sb[:, order]
+    raise ValueError("layout must be 'concat' or 'interleaved'")
+
+
+def quantize_blocks(v, scale_rounding="nearest"):
+    """v float32 [..., 32] finite -> (sbyte uint8 [...], codes uint8 [..., 32], X float64 [...]).
+    scale_rounding "nearest" is the floor rule of the header (the name matches the NVFP4 oracle's default)."""
+    if scale_rounding not in ("nearest", "up"):
+        raise ValueError("scale_rounding must be 'nearest' or 'up'")
     v = np.asarray(v)
     assert v.dtype == np.float32 and v.shape[-1] == G
     if not np.all(np.isfinite(v)):
@@ -41,6 +69,9 @@ def quantize_blocks(v):
     amax = np.abs(v).max(axis=-1).astype(np.float64)
     _, e = np.frexp(amax)                                   # amax = m * 2^e, m in [0.5, 1): floor(log2) = e - 1
     shared = np.where(amax > 0, e - 1 - EMAX_ELEM, 0)
+    if scale_rounding == "up":
+        # amax / 2^(e-1) in [1, 2), exact; above 1.5 the floor rule's 6 X falls short of amax
+        shared = shared + ((amax > 0) & (np.ldexp(amax, -(e - 1)) > 1.5))
     if np.any(shared < -E8M0_BIAS) or np.any(shared > 127):
         raise ValueError("shared exponent outside E8M0")
     sbyte = (shared + E8M0_BIAS).astype(np.uint8)
@@ -77,7 +108,7 @@ def _check_shape(K, S):
         raise ValueError("need K > 0, K % 32 == 0, 0 <= S <= K, S % 32 == 0")
 
 
-def quantize_act(Xa, perm, S):
+def quantize_act(Xa, perm, S, layout="concat", scale_rounding="nearest"):
     """Online activation quantizer (Section 3.2 steps (1)-(3)) in MXFP4.  Xa fp16 [M, K]."""
     Xa = np.asarray(Xa)
     assert Xa.dtype == np.float16 and Xa.ndim == 2
@@ -86,29 +117,31 @@ def quantize_act(Xa, perm, S):
     perm = np.asarray(perm)
     assert perm.shape == (K,)
     Xp = Xa[:, perm].astype(np.float32).reshape(M, K // G, G)
-    sb, codes, X = quantize_blocks(Xp)
+    sb, codes, X = quantize_blocks(Xp, scale_rounding)
     if S:
         o = (K - S) // G
         r = residual_blocks(Xp[:, o:], codes[:, o:], X[:, o:])
-        sb_r, codes_r, _ = quantize_blocks(r)
+        sb_r, codes_r, _ = quantize_blocks(r, scale_rounding)
         codes = np.concatenate([codes, codes_r], axis=1)
         sb = np.concatenate([sb, sb_r], axis=1)
+    codes, sb = _lay_out(codes, sb, K, S, layout)
     Kp = K + S
     return pack_nibbles(codes.reshape(M, Kp)), sb.reshape(M, Kp // G)
 
 
-def pack_weight(W, perm, S):
+def pack_weight(W, perm, S, layout="concat", scale_rounding="nearest"):
     """Offline weight packer: reorder, quantize, append a verbatim copy of the outlier blocks."""
     W = np.asarray(W)
     assert W.dtype == np.float16 and W.ndim == 2
     N, K = W.shape
     _check_shape(K, S)
     Wp = W[:, np.asarray(perm)].astype(np.float32).reshape(N, K // G, G)
-    sb, codes, _ = quantize_blocks(Wp)
+    sb, codes, _ = quantize_blocks(Wp, scale_rounding)
     if S:
         o = (K - S) // G
         codes = np.concatenate([codes, codes[:, o:]], axis=1)
         sb = np.concatenate([sb, sb[:, o:]], axis=1)
+    codes, sb = _lay_out(codes, sb, K, S, layout)
     Kp = K + S
     return pack_nibbles(codes.reshape(N, Kp)), sb.reshape(N, Kp // G)
 

@@ -14,10 +14,11 @@ LIB_PATH = os.environ.get("ARCQ_LIBRARY") or os.path.join(_HERE, "libarcq.so")  
 
 OK, INVALID_ARG, BAD_SHAPE, BAD_ALIGN, HIP_ERROR, WORKSPACE_TOO_SMALL = range(6)
 DTYPE_F16, DTYPE_F32 = 0, 1
+LAYOUT_INTERLEAVED, SCALE_ROUND_UP = 1, 2
 MAX_K = 65536
 
 # every symbol include/arcq.h declares: name -> (restype, argtypes)
-_i64, _f32, _vp, _sz = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+_i64, _f32, _vp, _sz, _u32 = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint32
 SIGNATURES = {
     "arcq_version": (ctypes.c_int, []),
     "arcq_last_error": (ctypes.c_char_p, []),
@@ -25,6 +26,11 @@ SIGNATURES = {
     "arcq_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _vp, _vp, _vp]),
     "arcq_rmsnorm_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _i64, _f32, _vp, _vp, _vp]),
     "arcq_pack_weight": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _vp, _vp, _vp]),
+    "arcq_quantize_act_ex": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _u32, _vp, _vp, _vp]),
+    "arcq_rmsnorm_quantize_act_ex": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _f32, _vp, _i64, _f32, _u32, _vp, _vp, _vp]),
+    "arcq_pack_weight_ex": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _f32, _u32, _vp, _vp, _vp]),
+    "arcq_mx_quantize_act_ex": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _u32, _vp, _vp, _vp]),
+    "arcq_mx_pack_weight_ex": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _u32, _vp, _vp, _vp]),
     "arcq_mx_packed_sizes": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
     "arcq_mx_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
     "arcq_mx_pack_weight": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
@@ -122,6 +128,31 @@ def arcq_pack_weight(w, perm, S, tensor_scale, codes=None, scales=None):
     return _quantize(lib().arcq_pack_weight, w, perm, S, tensor_scale, codes, scales)
 
 
+def _with_flags(lib_fn, flags):
+    """The *_ex entry points take `flags` right before the output pointers."""
+    def fn(xp, rows, K, ldx, permp, S_, sT, cp, sp, st):
+        return lib_fn(xp, rows, K, ldx, permp, S_, sT, int(flags), cp, sp, st)
+    return fn
+
+
+def arcq_quantize_act_ex(x, perm, S, tensor_scale, flags, codes=None, scales=None):
+    """arcq_quantize_act with the layout / scale-rounding variants (LAYOUT_INTERLEAVED | SCALE_ROUND_UP)."""
+    return _quantize(_with_flags(lib().arcq_quantize_act_ex, flags), x, perm, S, tensor_scale, codes, scales)
+
+
+def arcq_rmsnorm_quantize_act_ex(x, gamma, eps, perm, S, tensor_scale, flags, codes=None, scales=None):
+    assert gamma.is_cuda and gamma.dtype == torch.float16 and gamma.is_contiguous() and gamma.numel() == x.shape[1]
+    lib_fn = lib().arcq_rmsnorm_quantize_act_ex
+
+    def fn(xp, rows, K, ldx, permp, S_, sT, cp, sp, st):
+        return lib_fn(xp, rows, K, ldx, _ptr(gamma), float(eps), permp, S_, sT, int(flags), cp, sp, st)
+    return _quantize(fn, x, perm, S, tensor_scale, codes, scales)
+
+
+def arcq_pack_weight_ex(w, perm, S, tensor_scale, flags, codes=None, scales=None):
+    return _quantize(_with_flags(lib().arcq_pack_weight_ex, flags), w, perm, S, tensor_scale, codes, scales)
+
+
 def arcq_gemm_workspace_size(M, N, Kp):
     b = _sz(0)
     _check(lib().arcq_gemm_workspace_size(M, N, Kp, ctypes.byref(b)))
@@ -200,6 +231,20 @@ def arcq_mx_quantize_act(x, perm, S, codes=None, scales=None):
 
 def arcq_mx_pack_weight(w, perm, S, codes=None, scales=None):
     return _mx_quantize(lib().arcq_mx_pack_weight, w, perm, S, codes, scales)
+
+
+def _mx_with_flags(lib_fn, flags):
+    def fn(xp, rows, K, ldx, permp, S_, cp, sp, st):
+        return lib_fn(xp, rows, K, ldx, permp, S_, int(flags), cp, sp, st)
+    return fn
+
+
+def arcq_mx_quantize_act_ex(x, perm, S, flags, codes=None, scales=None):
+    return _mx_quantize(_mx_with_flags(lib().arcq_mx_quantize_act_ex, flags), x, perm, S, codes, scales)
+
+
+def arcq_mx_pack_weight_ex(w, perm, S, flags, codes=None, scales=None):
+    return _mx_quantize(_mx_with_flags(lib().arcq_mx_pack_weight_ex, flags), w, perm, S, codes, scales)
 
 
 def arcq_mx_gemm(a_codes, a_scales, w_codes, w_scales, out_dtype=torch.float16, y=None):

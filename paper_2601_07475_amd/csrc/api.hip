@@ -37,6 +37,12 @@ arcq_status check_scale(float s, const char* name) {
     return ARCQ_OK;
 }
 
+arcq_status check_flags(uint32_t flags, const char* who) {
+    if (flags & ~(uint32_t)(ARCQ_LAYOUT_INTERLEAVED | ARCQ_SCALE_ROUND_UP))
+        return fail(ARCQ_INVALID_ARG, "%s: unknown bits in flags = 0x%x", who, flags);
+    return ARCQ_OK;
+}
+
 arcq_status check_KS(int64_t K, int64_t S) {
     if (K <= 0 || (K % 16) != 0) return fail(ARCQ_BAD_SHAPE, "K = %lld: must be > 0 and a multiple of 16", (long long)K);
     if (K > ARCQ_MAX_K) return fail(ARCQ_BAD_SHAPE, "K = %lld exceeds ARCQ_MAX_K = %d", (long long)K, ARCQ_MAX_K);
@@ -47,9 +53,11 @@ arcq_status check_KS(int64_t K, int64_t S) {
 
 arcq_status quantize_entry(int mode, const char* who, const void* x, int64_t rows, int64_t K, int64_t ldx,
                            const int32_t* perm, int64_t S, float s_T, uint8_t* codes, uint8_t* scales,
-                           void* stream, bool norm = false, const void* gamma = nullptr, float eps = 0.0f) {
+                           void* stream, bool norm = false, const void* gamma = nullptr, float eps = 0.0f,
+                           uint32_t flags = 0) {
     clear_error();
     if (arcq_status st = check_KS(K, S)) return st;
+    if (arcq_status st = check_flags(flags, who)) return st;
     if (rows < 0 || rows > 0x7FFFFFFF) return fail(ARCQ_BAD_SHAPE, "%s: rows = %lld out of range", who, (long long)rows);
     if (ldx < K) return fail(ARCQ_BAD_SHAPE, "%s: leading dimension %lld < K = %lld", who, (long long)ldx, (long long)K);
     if (arcq_status st = check_scale(s_T, "tensor_scale")) return st;
@@ -61,7 +69,7 @@ arcq_status quantize_entry(int mode, const char* who, const void* x, int64_t row
         return fail(ARCQ_BAD_ALIGN, "%s: input must be 16-byte aligned with a leading dimension that is a multiple of 8", who);
     if (!aligned(codes, 8)) return fail(ARCQ_BAD_ALIGN, "%s: codes must be 8-byte aligned", who);
     if (!aligned(perm, 4)) return fail(ARCQ_BAD_ALIGN, "%s: perm must be 4-byte aligned", who);
-    return launch_quantize(mode, x, rows, K, ldx, perm, S, s_T, codes, scales, norm ? gamma : nullptr, eps,
+    return launch_quantize(mode, x, rows, K, ldx, perm, S, s_T, codes, scales, norm ? gamma : nullptr, eps, flags,
                            static_cast<hipStream_t>(stream));
 }
 
@@ -74,9 +82,11 @@ arcq_status check_KS_mx(int64_t K, int64_t S) {
 }
 
 arcq_status mx_quantize_entry(int mode, const char* who, const void* x, int64_t rows, int64_t K, int64_t ldx,
-                              const int32_t* perm, int64_t S, uint8_t* codes, uint8_t* scales, void* stream) {
+                              const int32_t* perm, int64_t S, uint8_t* codes, uint8_t* scales, void* stream,
+                              uint32_t flags = 0) {
     clear_error();
     if (arcq_status st = check_KS_mx(K, S)) return st;
+    if (arcq_status st = check_flags(flags, who)) return st;
     if (rows < 0 || rows > 0x7FFFFFFF) return fail(ARCQ_BAD_SHAPE, "%s: rows = %lld out of range", who, (long long)rows);
     if (ldx < K) return fail(ARCQ_BAD_SHAPE, "%s: leading dimension %lld < K = %lld", who, (long long)ldx, (long long)K);
     if (rows == 0) return ARCQ_OK;
@@ -85,7 +95,7 @@ arcq_status mx_quantize_entry(int mode, const char* who, const void* x, int64_t 
         return fail(ARCQ_BAD_ALIGN, "%s: input must be 16-byte aligned with a leading dimension that is a multiple of 8", who);
     if (!aligned(codes, 16)) return fail(ARCQ_BAD_ALIGN, "%s: codes must be 16-byte aligned", who);
     if (!aligned(perm, 16)) return fail(ARCQ_BAD_ALIGN, "%s: perm must be 16-byte aligned", who);
-    return launch_mx_quantize(mode, x, rows, K, ldx, perm, S, codes, scales, static_cast<hipStream_t>(stream));
+    return launch_mx_quantize(mode, x, rows, K, ldx, perm, S, codes, scales, flags, static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -124,6 +134,25 @@ arcq_status arcq_rmsnorm_quantize_act(const void* x, int64_t M, int64_t K, int64
 arcq_status arcq_pack_weight(const void* w, int64_t N, int64_t K, int64_t ldw, const int32_t* perm, int64_t S,
                              float tensor_scale, uint8_t* codes, uint8_t* scales, void* stream) {
     return quantize_entry(1, "arcq_pack_weight", w, N, K, ldw, perm, S, tensor_scale, codes, scales, stream);
+}
+
+arcq_status arcq_quantize_act_ex(const void* x, int64_t M, int64_t K, int64_t ldx, const int32_t* perm, int64_t S,
+                                 float tensor_scale, uint32_t flags, uint8_t* codes, uint8_t* scales, void* stream) {
+    return quantize_entry(0, "arcq_quantize_act_ex", x, M, K, ldx, perm, S, tensor_scale, codes, scales, stream,
+                          false, nullptr, 0.0f, flags);
+}
+
+arcq_status arcq_rmsnorm_quantize_act_ex(const void* x, int64_t M, int64_t K, int64_t ldx, const void* gamma, float eps,
+                                         const int32_t* perm, int64_t S, float tensor_scale, uint32_t flags,
+                                         uint8_t* codes, uint8_t* scales, void* stream) {
+    return quantize_entry(0, "arcq_rmsnorm_quantize_act_ex", x, M, K, ldx, perm, S, tensor_scale, codes, scales, stream,
+                          true, gamma, eps, flags);
+}
+
+arcq_status arcq_pack_weight_ex(const void* w, int64_t N, int64_t K, int64_t ldw, const int32_t* perm, int64_t S,
+                                float tensor_scale, uint32_t flags, uint8_t* codes, uint8_t* scales, void* stream) {
+    return quantize_entry(1, "arcq_pack_weight_ex", w, N, K, ldw, perm, S, tensor_scale, codes, scales, stream,
+                          false, nullptr, 0.0f, flags);
 }
 
 static arcq_status check_gemm_shape(int64_t M, int64_t N, int64_t Kp) {
@@ -215,6 +244,16 @@ arcq_status arcq_mx_quantize_act(const void* x, int64_t M, int64_t K, int64_t ld
 arcq_status arcq_mx_pack_weight(const void* w, int64_t N, int64_t K, int64_t ldw, const int32_t* perm, int64_t S,
                                 uint8_t* codes, uint8_t* scales, void* stream) {
     return mx_quantize_entry(1, "arcq_mx_pack_weight", w, N, K, ldw, perm, S, codes, scales, stream);
+}
+
+arcq_status arcq_mx_quantize_act_ex(const void* x, int64_t M, int64_t K, int64_t ldx, const int32_t* perm, int64_t S,
+                                    uint32_t flags, uint8_t* codes, uint8_t* scales, void* stream) {
+    return mx_quantize_entry(0, "arcq_mx_quantize_act_ex", x, M, K, ldx, perm, S, codes, scales, stream, flags);
+}
+
+arcq_status arcq_mx_pack_weight_ex(const void* w, int64_t N, int64_t K, int64_t ldw, const int32_t* perm, int64_t S,
+                                   uint32_t flags, uint8_t* codes, uint8_t* scales, void* stream) {
+    return mx_quantize_entry(1, "arcq_mx_pack_weight_ex", w, N, K, ldw, perm, S, codes, scales, stream, flags);
 }
 
 arcq_status arcq_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,

@@ -19,7 +19,8 @@ arcq_status check_launch(const char* what);
 // gamma != nullptr (mode 0 only): RMSNorm with that weight and eps in front of the quantizer.
 arcq_status launch_quantize(int mode, const void* x, int64_t rows, int64_t K, int64_t ldx,
                             const int32_t* perm, int64_t S, float s_T,
-                            uint8_t* codes, uint8_t* scales, const void* gamma, float eps, hipStream_t stream);
+                            uint8_t* codes, uint8_t* scales, const void* gamma, float eps, uint32_t flags,
+                            hipStream_t stream);
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t Kp);
 arcq_status launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
@@ -37,7 +38,7 @@ arcq_status launch_calib_select(const float* colmax, int64_t K, int32_t* perm, i
 
 // MXFP4 variant (blocks of 32, E8M0 scales, no tensor scale)
 arcq_status launch_mx_quantize(int mode, const void* x, int64_t rows, int64_t K, int64_t ldx, const int32_t* perm,
-                               int64_t S, uint8_t* codes, uint8_t* scales, hipStream_t stream);
+                               int64_t S, uint8_t* codes, uint8_t* scales, uint32_t flags, hipStream_t stream);
 arcq_status launch_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                            const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy,
                            hipStream_t stream);

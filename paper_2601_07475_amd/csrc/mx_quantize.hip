@@ -26,13 +26,17 @@ typedef float float2v __attribute__((ext_vector_type(2)));
 // One block of 32 fp32 values -> E8M0 byte, the scale X = 2^(byte - 127) and 32 codes (element i in
 // nibble i % 8 of c[i / 8]).  v_cvt_scalef32_pk_fp4_f32 with scale 1.0 rounds to nearest even on the
 // E2M1 grid, saturates at +-6 and keeps the sign of zero (checked on the GPU over every fp16 input).
-__device__ __forceinline__ void mx_quantize_block32(const float (&v)[32], uint32_t& sbyte, float& X, uint32_t (&c)[4]) {
+// scale_up (uniform over the launch): X is the smallest power of two with amax <= 6 X, one step above the
+// rule above exactly when the significand of amax exceeds 1.5, so that no element saturates.
+__device__ __forceinline__ void mx_quantize_block32(const float (&v)[32], uint32_t& sbyte, float& X, uint32_t (&c)[4],
+                                                    bool scale_up = false) {
     float amax = 0.0f;
 #pragma unroll
     for (int i = 0; i < 32; ++i) amax = fmaxf(amax, fabsf(v[i]));
     // amax is zero or a normal fp32 number: its exponent field is floor(log2) + 127
     const uint32_t ef = __float_as_uint(amax) >> 23;
-    sbyte = amax > 0.0f ? ef - 2u : 127u;
+    const uint32_t bump = scale_up && (__float_as_uint(amax) & 0x7FFFFFu) > 0x400000u ? 1u : 0u;
+    sbyte = amax > 0.0f ? ef - 2u + bump : 127u;
     X = __uint_as_float(sbyte << 23);
     const float inv = __uint_as_float((254u - sbyte) << 23);            // 1 / X, exact
 #pragma unroll
@@ -65,11 +69,15 @@ __device__ __forceinline__ void mx_residual_block32(const float (&v)[32], float 
 // BPT  32-channel blocks per lane (1 or 2);  MODE 0: activations (residual blocks), 1: weights (copies)
 // DB   two LDS row buffers (rows up to 36864 channels), else one.
 // STREAM  inputs far larger than the caches: rows are loaded with the non-temporal, system-scope policy.
+// flags   ARCQ_LAYOUT_INTERLEAVED: the partner of outlier block i sits right behind it (Appendix D);
+//         ARCQ_SCALE_ROUND_UP: see mx_quantize_block32.
 template <int BPT, int MODE, bool DB, bool STREAM>
 __global__ __launch_bounds__(1024) void mx_quantize_rows_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int rows, int K, int S, const int32_t* __restrict__ perm,
-    uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+    uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, uint32_t flags) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_row[];
+    const bool interleaved = (flags & ARCQ_LAYOUT_INTERLEAVED) != 0;
+    const bool scale_up = (flags & ARCQ_SCALE_ROUND_UP) != 0;
     constexpr int NPRE = 4 * BPT;           // 16-byte pieces of a row per lane
     const int tid = threadIdx.x, T = blockDim.x;
     const int nb = K >> 5, nbo = S >> 5, first_o = nb - nbo;
@@ -136,15 +144,17 @@ __global__ __launch_bounds__(1024) void mx_quantize_rows_kernel(
             }
             uint32_t sbyte, c[4];
             float X;
-            mx_quantize_block32(v, sbyte, X, c);
-            *reinterpret_cast<uint4*>(crow + 16 * (int64_t)b) = make_uint4(c[0], c[1], c[2], c[3]);
-            srow[b] = (uint8_t)sbyte;
-            if (b >= first_o) {
-                const int ba = nb + (b - first_o);
+            mx_quantize_block32(v, sbyte, X, c, scale_up);
+            const int io = b - first_o;                 // >= 0: outlier block number
+            const int bp = interleaved && io > 0 ? b + io : b;
+            *reinterpret_cast<uint4*>(crow + 16 * (int64_t)bp) = make_uint4(c[0], c[1], c[2], c[3]);
+            srow[bp] = (uint8_t)sbyte;
+            if (io >= 0) {
+                const int ba = interleaved ? bp + 1 : nb + io;
                 if (MODE == 0) {
                     float r[32];
                     mx_residual_block32(v, X, c, r);
-                    mx_quantize_block32(r, sbyte, X, c);
+                    mx_quantize_block32(r, sbyte, X, c, scale_up);
                 }
                 *reinterpret_cast<uint4*>(crow + 16 * (int64_t)ba) = make_uint4(c[0], c[1], c[2], c[3]);
                 srow[ba] = (uint8_t)sbyte;
@@ -161,7 +171,7 @@ __global__ __launch_bounds__(1024) void mx_quantize_rows_kernel(
 
 template <int BPT, int MODE, bool DB, bool STREAM>
 arcq_status launch_mx_t(int threads, size_t lds, const void* x, int64_t rows, int64_t K, int64_t ldx,
-                        const int32_t* perm, int64_t S, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+                        const int32_t* perm, int64_t S, uint8_t* codes, uint8_t* scales, uint32_t flags, hipStream_t stream) {
     auto kern = mx_quantize_rows_kernel<BPT, MODE, DB, STREAM>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -187,14 +197,14 @@ arcq_status launch_mx_t(int threads, size_t lds, const void* x, int64_t rows, in
     int64_t wgs = (int64_t)cus * cached_per_cu;
     if (wgs > rows) wgs = rows;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(threads), lds, stream, static_cast<const uint16_t*>(x), ldx,
-                       (int)rows, (int)K, (int)S, perm, codes, scales);
+                       (int)rows, (int)K, (int)S, perm, codes, scales, flags);
     return check_launch("mx_quantize_rows_kernel");
 }
 
 }  // namespace
 
 arcq_status launch_mx_quantize(int mode, const void* x, int64_t rows, int64_t K, int64_t ldx, const int32_t* perm,
-                               int64_t S, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+                               int64_t S, uint8_t* codes, uint8_t* scales, uint32_t flags, hipStream_t stream) {
     const int nb = (int)(K >> 5);
     const int bpt = (nb + 1023) / 1024;                       // 1 or 2 for K <= 65536
     const int threads = ((nb + bpt - 1) / bpt + 63) / 64 * 64;
@@ -203,8 +213,8 @@ arcq_status launch_mx_quantize(int mode, const void* x, int64_t rows, int64_t K,
     const size_t lds = db ? 2 * stride : stride;
     const bool stream_in = (uint64_t)rows * (uint64_t)K * 2 > (192ull << 20);   // beyond what the caches can hold
 #define ARCQ_MX_CASE2(B, D, ST) \
-    return mode == 0 ? launch_mx_t<B, 0, D, ST>(threads, lds, x, rows, K, ldx, perm, S, codes, scales, stream) \
-                     : launch_mx_t<B, 1, D, ST>(threads, lds, x, rows, K, ldx, perm, S, codes, scales, stream)
+    return mode == 0 ? launch_mx_t<B, 0, D, ST>(threads, lds, x, rows, K, ldx, perm, S, codes, scales, flags, stream) \
+                     : launch_mx_t<B, 1, D, ST>(threads, lds, x, rows, K, ldx, perm, S, codes, scales, flags, stream)
 #define ARCQ_MX_CASE(B, D) \
     if (stream_in) { ARCQ_MX_CASE2(B, D, true); } else { ARCQ_MX_CASE2(B, D, false); }
     if (db) {

@@ -12,19 +12,23 @@
 
 namespace arcq {
 
-// E4M3 byte (0x00..0x7E) nearest to u, ties to even mantissa, saturating at 448.
+// E4M3 byte (0x00..0x7E) for u, saturating at 448.  up == false: the nearest value, ties to even
+// mantissa; up == true: the smallest value not below u (the scale is never rounded down, which is
+// what the error analysis of Section 3.4 assumes: alpha >= 1).  `up` is uniform over the launch.
 // Precondition: u >= 0 and not NaN.
-__device__ __forceinline__ uint32_t e4m3_encode_sat(float u) {
+__device__ __forceinline__ uint32_t e4m3_encode_sat(float u, bool up = false) {
     if (!(u < 448.0f)) return 0x7Eu;
     if (u >= 0.015625f) {                       // normal range, >= 2^-6
         uint32_t bits = __float_as_uint(u);
-        // keep 3 mantissa bits: add half an ulp minus one plus the kept lsb, then truncate
-        bits += 0x7FFFFu + ((bits >> 20) & 1u);
+        // keep 3 mantissa bits: add half an ulp minus one plus the kept lsb (nearest even), or a whole
+        // ulp minus one (up), then truncate
+        bits += up ? 0xFFFFFu : 0x7FFFFu + ((bits >> 20) & 1u);
         return (bits >> 20) - (120u << 3);      // rebias exponent 127 -> 7
     }
     // subnormal range: multiples of 2^-9; the product is exact, rint is nearest-even;
     // a result of 8 is the byte of the smallest normal, 2^-6
-    return (uint32_t)__builtin_rintf(u * 512.0f);
+    const float t = u * 512.0f;
+    return (uint32_t)(up ? __builtin_ceilf(t) : __builtin_rintf(t));
 }
 
 // Value of an E4M3 byte in 0x00..0x7E as fp32 (exact).
@@ -44,12 +48,12 @@ __device__ __forceinline__ float e4m3_decode(uint32_t b) {
 // directly: rounding is symmetric, so this equals sign | round(|v| * inv).
 __device__ __forceinline__ void quantize_block16(const float (&v)[16], float s_T, float ginv,
                                                  uint32_t& sbyte, float& s,
-                                                 uint32_t& lo, uint32_t& hi) {
+                                                 uint32_t& lo, uint32_t& hi, bool scale_up = false) {
     float amax = 0.0f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
     float u = amax * ginv;
-    sbyte = e4m3_encode_sat(u);
+    sbyte = e4m3_encode_sat(u, scale_up);
     s = e4m3_decode(sbyte) * s_T;
     float inv = (s != 0.0f) ? 1.0f / s : 0.0f;
     lo = 0u;

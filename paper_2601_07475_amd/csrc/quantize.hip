@@ -54,6 +54,9 @@ typedef __attribute__((address_space(1))) const void global_void_t;
 //       1: gamma is copied once, coalesced, into LDS behind the row buffers and gathered from there
 //          (into registers when a lane owns one block, per row otherwise);
 //       2: no LDS left for it (very long rows): each lane gathers its gamma from global memory once.
+// flags (uniform, see arcq.h): ARCQ_LAYOUT_INTERLEAVED puts the partner block of outlier block i (its
+//       residual, or its copy for weights) right behind it, at block positions (K-S)/16 + 2i and + 2i + 1
+//       (Appendix D), instead of at K/16 + i; ARCQ_SCALE_ROUND_UP rounds every block scale up.
 // lds_stride = 32 * BPT * blockDim.x >= 2K: bytes of one row buffer, so that the lanes past
 // the end of a row (which re-read its last 16 bytes) land in padding.
 // Sum of v over each row of 16 lanes, in every lane of the row (data-parallel-primitive moves within
@@ -78,7 +81,7 @@ void quantize_rows_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int rows, int K, int S,
     const int32_t* __restrict__ perm, float s_T, float ginv,
     uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
-    const uint16_t* __restrict__ gamma, float eps, double delta, double inv_K, int force_exact) {
+    const uint16_t* __restrict__ gamma, float eps, double delta, double inv_K, int force_exact, uint32_t flags) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_row[];
     constexpr int NPRE = 2 * BPT;           // 16-byte pieces of a row per lane
     const int tid = threadIdx.x;
@@ -90,6 +93,8 @@ void quantize_rows_kernel(
     const uint32_t lds_stride = 32u * BPT * (uint32_t)T;
     const int64_t code_pitch = (int64_t)(K + S) >> 1;
     const int64_t scale_pitch = (int64_t)(K + S) >> 4;
+    const bool interleaved = (flags & ARCQ_LAYOUT_INTERLEAVED) != 0;
+    const bool scale_up = (flags & ARCQ_SCALE_ROUND_UP) != 0;
 
     int row = blockIdx.x;
     if (row >= rows) return;
@@ -304,15 +309,17 @@ void quantize_rows_kernel(
             }
             uint32_t sbyte, lo, hi;
             float s;
-            quantize_block16(v, s_T, ginv, sbyte, s, lo, hi);
-            *reinterpret_cast<uint2*>(crow + 8 * (int64_t)b) = make_uint2(lo, hi);
-            srow[b] = (uint8_t)sbyte;
-            if (b >= first_o) {
-                const int ba = nb + (b - first_o);      // augmented block index
+            quantize_block16(v, s_T, ginv, sbyte, s, lo, hi, scale_up);
+            const int io = b - first_o;                 // >= 0: outlier block number
+            const int bp = interleaved && io > 0 ? b + io : b;             // position of the primary block
+            *reinterpret_cast<uint2*>(crow + 8 * (int64_t)bp) = make_uint2(lo, hi);
+            srow[bp] = (uint8_t)sbyte;
+            if (io >= 0) {
+                const int ba = interleaved ? bp + 1 : nb + io;              // position of its partner
                 if (MODE == 0) {
                     float r[16];
                     residual_block16(v, s, lo, hi, r);
-                    quantize_block16(r, s_T, ginv, sbyte, s, lo, hi);
+                    quantize_block16(r, s_T, ginv, sbyte, s, lo, hi, scale_up);
                 }
                 *reinterpret_cast<uint2*>(crow + 8 * (int64_t)ba) = make_uint2(lo, hi);
                 srow[ba] = (uint8_t)sbyte;
@@ -343,7 +350,7 @@ int num_cu() {
 template <int BPT, int MODE, bool DB, bool STREAM, int NORM>
 arcq_status launch_t(int threads, int grid /* workgroups per CU, an estimate */, size_t lds, const void* x, int64_t rows, int64_t K,
                      int64_t ldx, const int32_t* perm, int64_t S, float s_T, float ginv,
-                     uint8_t* codes, uint8_t* scales, const void* gamma, float eps, hipStream_t stream) {
+                     uint8_t* codes, uint8_t* scales, const void* gamma, float eps, uint32_t flags, hipStream_t stream) {
     auto kern = quantize_rows_kernel<BPT, MODE, DB, STREAM, NORM>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -374,7 +381,7 @@ arcq_status launch_t(int threads, int grid /* workgroups per CU, an estimate */,
     const int force_exact = NORM != 0 && std::getenv("ARCQ_RMSNORM_EXACT_SUM") != nullptr;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(threads), lds, stream,
                        static_cast<const uint16_t*>(x), ldx, (int)rows, (int)K, (int)S, perm, s_T,
-                       ginv, codes, scales, static_cast<const uint16_t*>(gamma), eps, delta, 1.0 / (double)K, force_exact);
+                       ginv, codes, scales, static_cast<const uint16_t*>(gamma), eps, delta, 1.0 / (double)K, force_exact, flags);
     return check_launch("quantize_rows_kernel");
 }
 
@@ -382,7 +389,8 @@ arcq_status launch_t(int threads, int grid /* workgroups per CU, an estimate */,
 
 arcq_status launch_quantize(int mode, const void* x, int64_t rows, int64_t K, int64_t ldx,
                             const int32_t* perm, int64_t S, float s_T,
-                            uint8_t* codes, uint8_t* scales, const void* gamma, float eps, hipStream_t stream) {
+                            uint8_t* codes, uint8_t* scales, const void* gamma, float eps, uint32_t flags,
+                            hipStream_t stream) {
     const int nb = (int)(K >> 4);
     const int bpt = (nb + 1023) / 1024;                       // blocks per lane: 1..4 for K <= 65536
     const int threads = ((nb + bpt - 1) / bpt + 63) / 64 * 64;
@@ -406,7 +414,7 @@ arcq_status launch_quantize(int mode, const void* x, int64_t rows, int64_t K, in
     volatile float ginv = 1.0f / six_sT;
 
     const bool stream_in = (uint64_t)rows * (uint64_t)K * 2 > (192ull << 20);   // beyond what the caches can hold
-#define ARCQ_Q_ARGS threads, (int)grid, lds, x, rows, K, ldx, perm, S, s_T, ginv, codes, scales, gamma, eps, stream
+#define ARCQ_Q_ARGS threads, (int)grid, lds, x, rows, K, ldx, perm, S, s_T, ginv, codes, scales, gamma, eps, flags, stream
 #define ARCQ_Q_CASE2(B, D, ST)                                               \
     if (mode == 1) return launch_t<B, 1, D, ST, 0>(ARCQ_Q_ARGS);             \
     if (norm == 0) return launch_t<B, 0, D, ST, 0>(ARCQ_Q_ARGS);             \

@@ -162,3 +162,24 @@ def test_mx_argument_errors():
     assert mg(dt=9) == B.INVALID_ARG and mg(ac=None) == B.INVALID_ARG
     assert mg(ac=ctypes.c_void_p(0x10002)) == B.BAD_ALIGN and mg(y=ctypes.c_void_p(0x10002)) == B.BAD_ALIGN
     assert mg(M=0, ac=None, y=None) == B.OK
+
+
+def test_variant_entry_points_argument_errors():
+    L = B.lib()
+    for fn in (L.arcq_quantize_act_ex, L.arcq_pack_weight_ex):
+        assert fn(FAKE, 4, 512, 512, FAKE, 32, 1.0, 4, FAKE, FAKE, None) == B.INVALID_ARG      # unknown flag bit
+        assert b"flags" in L.arcq_last_error()
+        assert fn(FAKE, 4, 512, 512, FAKE, 32, 1.0, 0x80000001, FAKE, FAKE, None) == B.INVALID_ARG
+        assert fn(FAKE, 4, 520, 520, FAKE, 32, 1.0, 3, FAKE, FAKE, None) == B.BAD_SHAPE        # the plain rules still hold
+        assert fn(None, 4, 512, 512, FAKE, 32, 1.0, 3, FAKE, FAKE, None) == B.INVALID_ARG
+        for flags in (0, 1, 2, 3):
+            assert fn(None, 0, 512, 512, None, 32, 1.0, flags, None, None, None) == B.OK      # nothing to do
+    nq = L.arcq_rmsnorm_quantize_act_ex
+    assert nq(FAKE, 4, 512, 512, FAKE, 1e-5, FAKE, 32, 1.0, 8, FAKE, FAKE, None) == B.INVALID_ARG
+    assert nq(FAKE, 4, 512, 512, None, 1e-5, FAKE, 32, 1.0, 1, FAKE, FAKE, None) == B.INVALID_ARG   # gamma
+    assert nq(None, 0, 512, 512, None, 1e-5, None, 32, 1.0, 3, None, None, None) == B.OK
+    for fn in (L.arcq_mx_quantize_act_ex, L.arcq_mx_pack_weight_ex):
+        assert fn(FAKE, 4, 512, 512, FAKE, 32, 4, FAKE, FAKE, None) == B.INVALID_ARG
+        assert fn(FAKE, 4, 512, 512, FAKE, 16, 1, FAKE, FAKE, None) == B.BAD_SHAPE
+        assert fn(None, 0, 512, 512, None, 32, 3, None, None, None) == B.OK
+    assert (B.LAYOUT_INTERLEAVED, B.SCALE_ROUND_UP) == (1, 2)

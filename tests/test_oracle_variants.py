@@ -174,3 +174,66 @@ def test_variants_reject_unknown_names_and_S0_is_unchanged():
     a = A.quantize_act(c["X"], c["perm"], 0, c["sT_x"])
     b = A.quantize_act(c["X"], c["perm"], 0, c["sT_x"], layout="interleaved")
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+# ---- the same two variants on MXFP4 -----------------------------------------------------
+def test_mx_round_up_is_the_smallest_power_of_two_without_clipping():
+    from oracle import mxfp4 as MX
+    rng = np.random.default_rng(6)
+    v = (rng.standard_normal((400, 32)) * np.exp(rng.standard_normal((400, 1)) * 3)).astype(np.float16)
+    v[0] = 0
+    v[1] = np.float16(2.0 ** -24)
+    v[2, :] = np.float16(6.0)            # exactly 1.5 * 2^2: the floor rule already holds it
+    v[3, :] = np.float16(6.004)          # just above
+    v[4] = np.float16(65504.0)
+    v = v.astype(np.float32)
+    sb, codes, X = MX.quantize_blocks(v, "up")
+    sb_f, _, X_f = MX.quantize_blocks(v)
+    # the defining inequalities, in exact rationals, block by block
+    for i in range(len(v)):
+        amax = max(Fr(float(t)) for t in np.abs(v[i]))
+        Xi = Fr(2) ** (int(sb[i]) - 127)
+        if amax == 0:
+            assert sb[i] == 127
+            continue
+        assert amax <= 6 * Xi and amax > 3 * Xi               # X / 2 would clip
+        for t, c in zip(v[i], codes[i]):
+            assert (c & 7) == brute.e2m1_nearest(abs(Fr(float(t))) / Xi) and (c >> 3) == int(np.signbit(t))
+    assert sb[2] == sb_f[2] and sb[3] == sb_f[3] + 1
+    d = sb.astype(int) - sb_f.astype(int)
+    assert set(d.tolist()) == {0, 1} and 0.2 < d.mean() < 0.8
+    # nothing clips: every element is within half a grid step
+    deq = F.e2m1_decode(codes) * X[:, None]
+    step = np.where(np.abs(deq) >= 4 * X[:, None], 2.0, np.where(np.abs(deq) >= 2 * X[:, None], 1.0, 0.5)) * X[:, None]
+    assert np.all(np.abs(v - deq) <= step / 2)
+    # the largest error of a block is at most amax / 6 (alpha <= 2: X < amax / 3), i.e. half the top step
+    amax = np.abs(v).max(axis=1)
+    assert np.all(np.abs(v - deq).max(axis=1) <= X)
+
+
+def test_mx_interleaved_layout_is_a_block_permutation():
+    from oracle import mxfp4 as MX
+    assert MX.interleaved_order(64, 64).tolist() == [0, 2, 1, 3]
+    assert MX.interleaved_order(128, 64).tolist() == [0, 1, 2, 4, 3, 5]
+    wl = wk.Workload("t", 10, 256, 12, 96, 5, "const50", 0.02, 4)
+    c = wk.make_case(wl)
+    X, W, perm, S = c["X"], c["W"], c["perm"], 96
+    nb, no = 256 // 32, 96 // 32
+    for rounding in ("nearest", "up"):
+        cc, cs = MX.quantize_act(X, perm, S, scale_rounding=rounding)
+        ic, isc = MX.quantize_act(X, perm, S, layout="interleaved", scale_rounding=rounding)
+        wc, wsc = MX.pack_weight(W, perm, S, scale_rounding=rounding)
+        iwc, iwsc = MX.pack_weight(W, perm, S, layout="interleaved", scale_rounding=rounding)
+        for (pc, ps, qc, qs) in ((cc, cs, ic, isc), (wc, wsc, iwc, iwsc)):
+            for b in range(nb - no):
+                assert np.array_equal(qc[:, 16 * b:16 * b + 16], pc[:, 16 * b:16 * b + 16]) and np.array_equal(qs[:, b], ps[:, b])
+            for i in range(no):
+                for src, dst in ((nb - no + i, nb - no + 2 * i), (nb + i, nb - no + 2 * i + 1)):
+                    assert np.array_equal(qc[:, 16 * dst:16 * dst + 16], pc[:, 16 * src:16 * src + 16])
+                    assert np.array_equal(qs[:, dst], ps[:, src])
+        Yc, Yi = MX.gemm(cc, cs, wc, wsc), MX.gemm(ic, isc, iwc, iwsc)
+        assert np.allclose(Yc, Yi, rtol=0, atol=1e-12 * np.abs(Yc).max())
+    with pytest.raises(ValueError):
+        MX.quantize_act(X, perm, S, layout="x")
+    with pytest.raises(ValueError):
+        MX.quantize_act(X, perm, S, scale_rounding="x")
