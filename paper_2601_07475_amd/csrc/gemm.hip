@@ -586,8 +586,10 @@ arcq_status launch_skinny(const uint8_t* a_codes, const uint8_t* a_scales, const
 
 // Number of runs the reduction dimension is cut into (1: no split).  A function of the shape alone,
 // so that the workspace a caller sizes beforehand matches what the launch uses.  Problems of more
-// than 128 rows with too few 128 x 128 tiles to occupy the chip split K' until about 256 workgroups
-// exist, each run at least four stages (512 k) long.
+// than 128 rows with too few 128 x 128 tiles to occupy the chip split K' into runs of at least four
+// stages (256 k).  The number of runs minimises a cost in units of one stage time of a tile (about
+// 1.3 us): rounds of workgroups over the 256 CUs times the stages of a run, plus, when split, the
+// write and read of the fp32 partial results at about 3 TB/s.
 int split_k(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nbk = Kp >> 4;
     if (M <= 128 || (nbk & 3) != 0 || nbk < 8) return 1;
@@ -595,9 +597,19 @@ int split_k(int64_t M, int64_t N, int64_t Kp) {
     const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
     if (tiles > 128) return 1;
     const int64_t nstage = (nbk + 7) >> 3;
-    int64_t splits = std::min<int64_t>(8, (256 + tiles - 1) / tiles);
-    splits = std::min(splits, nstage / 4);
-    return splits < 2 ? 1 : (int)splits;
+    const int64_t max_splits = std::min<int64_t>(8, nstage / 4);
+    int best = 1;
+    double best_cost = 0.0;
+    for (int64_t sp = 1; sp <= max_splits; ++sp) {
+        const double rounds = (double)((tiles * sp + 255) / 256);
+        double cost = rounds * (double)((nstage + sp - 1) / sp);
+        if (sp > 1) cost += (double)sp * (double)M * (double)N * 8.0 / 4.0e6;
+        if (sp == 1 || cost < best_cost) {
+            best = (int)sp;
+            best_cost = cost;
+        }
+    }
+    return best;
 }
 
 template <typename OutT>

@@ -266,9 +266,9 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     # batched decode: 2, 4 and 8 tiles of 16 activation rows on the weight-streaming kernel, S from 0 to K
     (20, 300, 512, 32), (32, 1000, 1024, 0), (33, 77, 2048, 2048), (64, 4097, 256, 64), (100, 260, 4160, 64),
     (128, 45, 160, 32), (17, 14336, 512, 512), (48, 2048, 4096, 1024),
-    # more than 128 rows but few tiles: the reduction dimension is split (8, 8, 4 runs; the last run of the third
+    # more than 128 rows but few tiles: the reduction dimension is split into 2 to 8 runs (the last run of the third
     # ends with a half stage) and the partial results are added by a second kernel; the fourth is too short to split
-    (256, 512, 4096, 256), (300, 260, 4160, 64), (130, 129, 2048, 64), (200, 140, 576, 64),
+    (256, 512, 4096, 256), (300, 260, 4160, 64), (130, 129, 2048, 64), (200, 140, 576, 64), (384, 1000, 1024, 64),
     # ragged edges in every tile configuration of the staged kernel: 128 x 256 tiles (8 waves), 256 x 256 tiles
     (1990, 4070, 256, 64), (4000, 4100, 128, 64),
 ]
