@@ -174,6 +174,18 @@ arcq_status arcq_check_perm(const int32_t* perm, int64_t K, uint8_t* flags,
                             int* result_host, void* stream);
 
 /*
+ * Diagnostic for measurements (no part of the method): enqueues a kernel in which 4096 waves (four per
+ * SIMD on 256 CUs) each issue 4 * iters fp16 32x32x16 matrix instructions on register operands, the
+ * instruction arcq_gemm is built on, with no memory traffic in the loop.  Timing the launch gives the
+ * matrix rate this machine sustains, the ceiling to read arcq_gemm's roofline fraction against.
+ * iters   1 .. 2^20
+ * sink    device, ARCQ_PROBE_SINK_FLOATS floats, written (keeps the loop alive), 4-byte aligned
+ * flop_host  host pointer: receives the floating-point operations of one launch
+ */
+#define ARCQ_PROBE_SINK_FLOATS 262144
+arcq_status arcq_probe_mfma_f16(int iters, float* sink, double* flop_host, void* stream);
+
+/*
  * Offline calibration (Section 3.2 "Adaptive Outlier Identification"), two calls.
  *
  * arcq_calib_absmax folds one batch of calibration activations into the running per-channel

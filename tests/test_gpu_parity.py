@@ -556,3 +556,13 @@ def test_mx_full_size_llama8b_qproj():
     rows = np.random.default_rng(1).choice(X.shape[0], 48, replace=False)
     Yref = MX.gemm(want_c[rows], want_s[rows], owc, owsc)
     assert norm_err(Y[rows], Yref) <= GEMM_TOL_F16
+
+
+def test_matrix_rate_probe_runs_and_counts_its_work():
+    say("arcq_probe_mfma_f16")
+    sink = torch.full((B.PROBE_SINK_FLOATS,), float("nan"), dtype=torch.float32, device="cuda")
+    flop = B.arcq_probe_mfma_f16(3, sink)
+    torch.cuda.synchronize()
+    assert flop == 4096 * 3 * 4 * 2 * 32 * 32 * 16
+    out = sink.cpu().numpy()
+    assert np.all(np.isfinite(out)) and np.any(out != 0)

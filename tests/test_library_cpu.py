@@ -184,3 +184,13 @@ def test_variant_entry_points_argument_errors():
         assert fn(FAKE, 4, 512, 512, FAKE, 16, 1, FAKE, FAKE, None) == B.BAD_SHAPE
         assert fn(None, 0, 512, 512, None, 32, 3, None, None, None) == B.OK
     assert (B.LAYOUT_INTERLEAVED, B.SCALE_ROUND_UP) == (1, 2)
+
+
+def test_probe_argument_errors():
+    L = B.lib()
+    fl = ctypes.c_double(0)
+    assert L.arcq_probe_mfma_f16(0, FAKE, ctypes.byref(fl), None) == B.INVALID_ARG
+    assert L.arcq_probe_mfma_f16(1 << 21, FAKE, ctypes.byref(fl), None) == B.INVALID_ARG
+    assert L.arcq_probe_mfma_f16(10, None, ctypes.byref(fl), None) == B.INVALID_ARG
+    assert L.arcq_probe_mfma_f16(10, FAKE, None, None) == B.INVALID_ARG
+    assert L.arcq_probe_mfma_f16(10, ctypes.c_void_p(0x10002), ctypes.byref(fl), None) == B.BAD_ALIGN
