@@ -138,9 +138,12 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
         mac = torch.empty((wl.M, Kp // 2), dtype=torch.uint8, device="cuda")
         masc = torch.empty((wl.M, Kp // 32), dtype=torch.uint8, device="cuda")
 
+        mx_quant = B.prepare_mx_quantize_act(X, perm, S, mac, masc)
+        mx_gemm = B.prepare_mx_gemm(mac, masc, mwc, mwsc, Y)
+
         def mx_step():
-            B.arcq_mx_quantize_act(X, perm, S, codes=mac, scales=masc)
-            B.arcq_mx_gemm(mac, masc, mwc, mwsc, y=Y)
+            mx_quant()
+            mx_gemm()
         for _ in range(3):
             mx_step()
         torch.cuda.synchronize()
@@ -154,7 +157,7 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
         out["mx_step_ms"] = e0.elapsed_time(e1) / n
         e0.record()
         for _ in range(n):
-            B.arcq_mx_gemm(mac, masc, mwc, mwsc, y=Y)
+            mx_gemm()
         e1.record()
         torch.cuda.synchronize()
         out["mx_gemm_ms"] = e0.elapsed_time(e1) / n

@@ -307,6 +307,29 @@ def prepare_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_
     return call
 
 
+def prepare_mx_quantize_act(x, perm, S, codes, scales):
+    """Same for arcq_mx_quantize_act."""
+    rows, K = x.shape
+    fn = lib().arcq_mx_quantize_act
+    args = (_ptr(x), rows, K, x.stride(0) if rows > 1 else K, _ptr(perm), S, _ptr(codes), _ptr(scales), _stream())
+
+    def call():
+        _check(fn(*args))
+    return call
+
+
+def prepare_mx_gemm(a_codes, a_scales, w_codes, w_scales, y):
+    """Same for arcq_mx_gemm."""
+    M, N, Kp = a_codes.shape[0], w_codes.shape[0], a_codes.shape[1] * 2
+    fn = lib().arcq_mx_gemm
+    args = (_ptr(a_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), M, N, Kp, _ptr(y),
+            DTYPE_F16 if y.dtype == torch.float16 else DTYPE_F32, y.stride(0) if M > 1 else N, _stream())
+
+    def call():
+        _check(fn(*args))
+    return call
+
+
 PROBE_SINK_FLOATS = 262144
 
 

@@ -303,7 +303,12 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     // stage s (its buffer was last read in stage s-1, which every wave left before the barrier
     // that opened stage s), so no wave ever queues a burst of memory instructions.
     constexpr int G = WM + WN;                 // fragments per k-step
-    constexpr int P = (WM * WN) / 2;           // MFMA pairs per k-step
+    // MFMAs per group: after every group the decode of G / P fragments is placed.  With few MFMAs per
+    // fragment (2 x 2 fragments: ten vector instructions per MFMA) single MFMAs interleave best with the
+    // vector work (a register-only model of this loop ran 10 % faster with singles than with pairs);
+    // with 4 x 4 fragments pairs and singles measure the same.
+    constexpr int MPG = (WM * WN >= 16) ? 2 : 1;
+    constexpr int P = (WM * WN) / MPG;         // groups per k-step
     uint4 ca[2][WM], cw[2][WN];
     uint32_t sa[2][WM], sw[2][WN];
     half8 fa[2][WM], fw[2][WN];
@@ -369,7 +374,7 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int q = 2 * p; q < 2 * p + 2; ++q) {
+                for (int q = MPG * p; q < MPG * p + MPG; ++q) {
                     const int i = q / WN, j = q % WN;
                     // weights as the row operand: see store_tile_swapped
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[x & 1][j], fa[x & 1][i], acc[i][j], 0, 0, 0);
