@@ -46,6 +46,23 @@ __device__ __forceinline__ half8 decode8(uint32_t c, half2v sc) {
     return out;
 }
 
+// The same with the scale taken from one half of a register that holds the fp16 scales of two blocks:
+// a byte permute spreads two scale bytes (bits 0-7 and 8-15 of s) to bits 0-7 and 16-23, one shift puts
+// both in place, and the packed multiplies broadcast the half they need through their operand-select
+// modifiers.  Two vector instructions per two blocks (four k-steps) instead of two per k-step.
+__device__ __forceinline__ uint32_t scale_halves(uint32_t s) {
+    return __builtin_amdgcn_perm(0u, s, 0x0C010C00u) << 7;
+}
+__device__ __forceinline__ half8 decode8_half(uint32_t c, uint32_t halves, int hi) {
+    const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(hi ? halves >> 16 : halves));
+    const half2v sc = {s, s};
+    half2v p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 0) * sc;
+    half2v p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 1) * sc;
+    half2v p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 2) * sc;
+    half2v p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 3) * sc;
+    half8 out = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+    return out;
+}
 
 // Accumulates blocks [b_begin, b_end) straight from global memory (no staging): used for the
 // K' tail of the staged kernel and as the whole loop of the fallback kernel.  One iteration
@@ -237,7 +254,7 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     // Offsets are recomputed per copy (a handful of ALU operations per stage) rather than kept
     // in registers: the accumulators leave this kernel 256 registers and it needs most of them.
     // (s & 3) and the row swizzle repeat every 64 slots, so one value serves every copy
-    const uint32_t lp_ = (uint32_t)((tid & 3) ^ ((tid >> 3) & 3));
+    const uint32_t lp_ = (uint32_t)((tid & 3) ^ ((tid >> 4) & 3));
     const uint32_t adj_c0 = lp_ * 16u, adj_c1 = (lp_ & 1u) * 16u, adj_s = (uint32_t)(tid & 1) * 4u;
     const int crow = tid >> 2, srow = tid >> 1; // row of this thread inside a copy of NT/4 code rows / NT/2 scale rows
     const uint32_t cpitch32 = (uint32_t)nbk * 8u, spitch32 = (uint32_t)nbk;
@@ -278,7 +295,7 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     // ---- LDS read offsets of this lane inside a stage.  Fragment i of a wave is 32 rows (2048
     // bytes of codes, 256 of scales) further on, a constant folded into the instruction; the
     // swizzle (row >> 1) & 3 only depends on lane % 32 because the other terms are multiples of 32.
-    const uint32_t swz = (uint32_t)(r >> 1) & 3u;
+    const uint32_t swz = (uint32_t)(r >> 2) & 3u;
     const uint32_t rd_a = C::A_CODES + (wrow0 + r) * 64, rd_w = C::W_CODES + (wcol0 + r) * 64;
     const uint32_t rd_as = C::A_SCALES + (wrow0 + r) * 8 + 2 * h, rd_ws = C::W_SCALES + (wcol0 + r) * 8 + 2 * h;
     const uint32_t piece0 = 16u * ((uint32_t)h ^ swz), piece1 = 16u * ((2u + (uint32_t)h) ^ swz);
@@ -320,12 +337,12 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
             ca[u][i] = *reinterpret_cast<const uint4*>(pa + i * 2048);
-            sa[u][i] = *reinterpret_cast<const uint16_t*>(psa + i * 256);
+            sa[u][i] = scale_halves(*reinterpret_cast<const uint16_t*>(psa + i * 256));
         }
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             cw[u][j] = *reinterpret_cast<const uint4*>(pw + j * 2048);
-            sw[u][j] = *reinterpret_cast<const uint16_t*>(psw + j * 256);
+            sw[u][j] = scale_halves(*reinterpret_cast<const uint16_t*>(psw + j * 256));
         }
     };
     auto decode_frag = [&](int gidx, int x) {   // fragment gidx of k-step x (0..7) into slot x & 1
@@ -333,12 +350,12 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
         if (gidx < WM) {
             const uint4 c4 = ca[u][gidx];
             const uint32_t c = t == 0 ? c4.x : t == 1 ? c4.y : t == 2 ? c4.z : c4.w;
-            fa[d][gidx] = decode8(c, scale_pair((t < 2) ? (sa[u][gidx] & 0xFFu) : (sa[u][gidx] >> 8)));
+            fa[d][gidx] = decode8_half(c, sa[u][gidx], t >> 1);
         } else {
             const int j = gidx - WM;
             const uint4 c4 = cw[u][j];
             const uint32_t c = t == 0 ? c4.x : t == 1 ? c4.y : t == 2 ? c4.z : c4.w;
-            fw[d][j] = decode8(c, scale_pair((t < 2) ? (sw[u][j] & 0xFFu) : (sw[u][j] >> 8)));
+            fw[d][j] = decode8_half(c, sw[u][j], t >> 1);
         }
     };
 
