@@ -50,8 +50,9 @@ __device__ __forceinline__ half8 decode8(uint32_t c, half2v sc) {
 // a byte permute spreads two scale bytes (bits 0-7 and 8-15 of s) to bits 0-7 and 16-23, one shift puts
 // both in place, and the packed multiplies broadcast the half they need through their operand-select
 // modifiers.  Two vector instructions per two blocks (four k-steps) instead of two per k-step.
-__device__ __forceinline__ uint32_t scale_halves(uint32_t s) {
-    return __builtin_amdgcn_perm(0u, s, 0x0C010C00u) << 7;
+// `sel` picks the two bytes: 0x0C010C00 takes bytes 0 and 1 of s, 0x0C030C02 bytes 2 and 3.
+__device__ __forceinline__ uint32_t scale_halves(uint32_t s, uint32_t sel) {
+    return __builtin_amdgcn_perm(0u, s, sel) << 7;
 }
 __device__ __forceinline__ half8 decode8_half(uint32_t c, uint32_t halves, int hi) {
     const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(hi ? halves >> 16 : halves));
@@ -181,7 +182,9 @@ __global__ __launch_bounds__(256) void gemm_direct_kernel(
 //
 // LDS layout of one stage (bytes):  A codes [BM][64] | W codes [BN][64] | A scales [BM][8] |
 // W scales [BN][8].  The four 16-byte pieces of a row's codes are stored XOR-swizzled with
-// (row >> 1) & 3 so that the 16-byte reads of 8 consecutive rows fall in 8 different bank groups.
+// (row >> 2) & 3: the LDS serves a 16-byte read of 16 consecutive lanes per clock from 64 banks, rows
+// are 64 bytes apart, so 16 consecutive rows must land on 16 different 16-byte bank groups (measured: a
+// swizzle with a period of 8 rows spent half of the LDS-active cycles on bank conflicts).
 // A wave-wide DMA instruction writes lane l to (uniform base) + 16 l, so the swizzle is applied
 // by choosing which global piece each lane fetches.
 template <int WM, int WN, int GM, int GN>
@@ -294,10 +297,14 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
 
     // ---- LDS read offsets of this lane inside a stage.  Fragment i of a wave is 32 rows (2048
     // bytes of codes, 256 of scales) further on, a constant folded into the instruction; the
-    // swizzle (row >> 1) & 3 only depends on lane % 32 because the other terms are multiples of 32.
+    // swizzle (row >> 2) & 3 only depends on lane % 32 because the other terms are multiples of 32.
     const uint32_t swz = (uint32_t)(r >> 2) & 3u;
     const uint32_t rd_a = C::A_CODES + (wrow0 + r) * 64, rd_w = C::W_CODES + (wcol0 + r) * 64;
-    const uint32_t rd_as = C::A_SCALES + (wrow0 + r) * 8 + 2 * h, rd_ws = C::W_SCALES + (wcol0 + r) * 8 + 2 * h;
+    // a lane reads the whole 4-byte scale word of its row and 64-k half stage (both halves of the wave read
+    // the same word, which the LDS broadcasts; two-byte reads of its two halves count as a bank conflict)
+    // and picks its two bytes with the byte selector of the permute
+    const uint32_t rd_as = C::A_SCALES + (wrow0 + r) * 8, rd_ws = C::W_SCALES + (wcol0 + r) * 8;
+    const uint32_t scale_sel = h ? 0x0C030C02u : 0x0C010C00u;
     const uint32_t piece0 = 16u * ((uint32_t)h ^ swz), piece1 = 16u * ((2u + (uint32_t)h) ^ swz);
 
     float16v acc[WM][WN];
@@ -337,12 +344,12 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
             ca[u][i] = *reinterpret_cast<const uint4*>(pa + i * 2048);
-            sa[u][i] = scale_halves(*reinterpret_cast<const uint16_t*>(psa + i * 256));
+            sa[u][i] = scale_halves(*reinterpret_cast<const uint32_t*>(psa + i * 256), scale_sel);
         }
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             cw[u][j] = *reinterpret_cast<const uint4*>(pw + j * 2048);
-            sw[u][j] = scale_halves(*reinterpret_cast<const uint16_t*>(psw + j * 256));
+            sw[u][j] = scale_halves(*reinterpret_cast<const uint32_t*>(psw + j * 256), scale_sel);
         }
     };
     auto decode_frag = [&](int gidx, int x) {   // fragment gidx of k-step x (0..7) into slot x & 1

@@ -35,7 +35,9 @@ __device__ __forceinline__ float16v mfma_mx(const uint4& a, const uint4& b, cons
 // global -> LDS with global_load_lds through a ring of NUNIT buffers (2 for the 256 x 256 tile: 2 x 68 KB),
 // one barrier per unit.  LDS layout of one unit: A codes [BM][128] | W codes [BN][128] | A scales [BM][8] |
 // W scales [BN][8] (regions padded to whole workgroup-wide copies).  The eight pieces of a row are stored
-// XOR-swizzled with row & 7 (a 16-byte read by 8 consecutive rows then covers all 32 banks), applied by
+// XOR-swizzled with (row >> 1) & 7: the LDS serves a 16-byte read of 16 consecutive lanes per clock from
+// 64 banks, rows are 128 bytes apart, so 16 consecutive rows must land on 16 different 16-byte bank groups
+// (measured: a swizzle with a period of 8 rows spent 44 % of its LDS cycles on bank conflicts); applied by
 // choosing which global piece a lane fetches (a wave-wide copy writes lane l to base + 16 l).
 // When K' is an odd multiple of 128 the last unit is half a unit: its copies re-fetch the first half
 // for the missing second half (never used, in bounds).
@@ -87,7 +89,7 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
 
     // ---- copies: thread -> (row, piece) of a workgroup-wide copy; 8 lanes fetch one row's 128 bytes
     const uint32_t cpitch = (uint32_t)nb * 16u, spitch = (uint32_t)nb;
-    const uint32_t lp = (uint32_t)((tid & 7) ^ ((tid >> 3) & 7));               // global piece this lane fetches
+    const uint32_t lp = (uint32_t)((tid & 7) ^ ((tid >> 4) & 7));               // global piece this lane fetches
     const int crow = tid >> 3, srow = tid >> 1;
     const uint32_t wave_slot = __builtin_amdgcn_readfirstlane((uint32_t)(tid & ~63));
     const uint32_t lds0 = lds_address(lds);
@@ -117,8 +119,9 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
     };
 
     // ---- LDS read offsets of this lane: k-step t of a unit takes piece 2t + h of its rows, stored at
-    // physical position (2t + h) ^ (row & 7); row & 7 = r & 7 because the other terms are multiples of 32
-    const uint32_t swz = (uint32_t)r & 7u;
+    // physical position (2t + h) ^ ((row >> 1) & 7), which only depends on r because the other terms of the
+    // row are multiples of 32
+    const uint32_t swz = (uint32_t)(r >> 1) & 7u;
     const uint32_t rd_a = C::A_CODES + (wrow0 + r) * 128, rd_w = C::W_CODES + (wcol0 + r) * 128;
     const uint32_t rd_as = C::A_SCALES + (wrow0 + r) * 8, rd_ws = C::W_SCALES + (wcol0 + r) * 8;
     uint32_t pc[4];
