@@ -428,8 +428,16 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     wait_vmcnt<0>();                            // no copy may still be in flight when the LDS is released
 
     const int m0 = wg_m0 + wrow0, n0 = wg_n0 + wcol0;
-    const bool vec_ok = (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
-    store_tile_swapped<WM, WN>(acc, m0, n0, r, h, M, N, alpha, y + (int64_t)split * split_stride, ldy, vec_ok);
+    if constexpr (std::is_same<OutT, _Float16>::value) {
+        static_assert(epilogue_lds_bytes(WN) * GM * GN <= C::LDS_BYTES, "one epilogue region per wave must fit the operand ring");
+        wg_barrier();                           // every wave has read its last operands: the ring is free
+        const bool vec_ok = (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
+        store_tile_f16_via_lds<WM, WN>(acc, lds + wave * epilogue_lds_bytes(WN), m0, n0, lane, M, N, alpha,
+                                       y + (int64_t)split * split_stride, ldy, vec_ok);
+    } else {
+        const bool vec_ok = (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
+        store_tile_swapped<WM, WN>(acc, m0, n0, r, h, M, N, alpha, y + (int64_t)split * split_stride, ldy, vec_ok);
+    }
 }
 
 // y = alpha * (sum of the `splits` fp32 partial results [M, N], added in index order).

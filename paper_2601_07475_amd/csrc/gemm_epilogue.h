@@ -48,4 +48,67 @@ __device__ __forceinline__ void store_tile_swapped(const float16v (&acc)[WM][WN]
     }
 }
 
+// fp16 output through the LDS, so that the global stores are whole lines: in the accumulator layout a
+// store instruction of a wave touches 32 different rows with 16 bytes each, and the address unit of a
+// CU spends about as long on such an instruction as on four that write eight full 128-byte lines; on
+// tiles with a short reduction dimension the direct epilogue took several microseconds per tile.
+// A wave writes two fragment rows (64 rows x 32 WN columns of fp16) into its own LDS region, row pitch
+// 64 WN + 16 bytes (the padding spreads the 32 rows of one write over the banks and keeps every row
+// 16-byte aligned), and reads them back row-contiguous, 16 bytes per lane: one store instruction then
+// covers 16 / WN whole rows.
+// lds_wave: this wave's region of epilogue_lds_bytes(WN) bytes, 16-byte aligned, not in use by anyone
+// else (the caller synchronises the workgroup after the last read of the operand buffers).  Everything
+// else as above.
+constexpr int epilogue_lds_bytes(int WN) { return 64 * (64 * WN + 16); }
+
+template <int WM, int WN>
+__device__ __forceinline__ void store_tile_f16_via_lds(const float16v (&acc)[WM][WN], uint8_t* lds_wave, int m0, int n0,
+                                                       int lane, int M, int N, float alpha, _Float16* __restrict__ y,
+                                                       int64_t ldy, bool vec_ok) {
+    static_assert(WM % 2 == 0, "two fragment rows at a time");
+    typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+    typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+    constexpr int ROWB = 64 * WN + 16;
+    constexpr int LPR = 4 * WN;             // lanes per row when reading back (16 bytes each)
+    constexpr int RPI = 64 / LPR;           // rows per store instruction
+    const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int i0 = 0; i0 < WM; i0 += 2) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const half4v v = {(_Float16)(acc[i0 + ii][j][4 * g] * alpha), (_Float16)(acc[i0 + ii][j][4 * g + 1] * alpha),
+                                      (_Float16)(acc[i0 + ii][j][4 * g + 2] * alpha), (_Float16)(acc[i0 + ii][j][4 * g + 3] * alpha)};
+                    *reinterpret_cast<half4v*>(lds_wave + (32 * ii + r) * ROWB + 2 * (32 * j + 8 * g + 4 * h)) = v;
+                }
+        // the reads below take what other lanes of this wave wrote: LDS operations of a wave complete in order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int k = 0; k < 64 / RPI; ++k) {
+            const int row = k * RPI + lane / LPR, chunk = lane % LPR;
+            const half8v v = *reinterpret_cast<const half8v*>(lds_wave + row * ROWB + 16 * chunk);
+            const int m = m0 + 32 * i0 + row, n = n0 + 8 * chunk;
+            if (m >= M) continue;
+            _Float16* dst = y + (int64_t)m * ldy + n;
+            if (vec_ok && n + 7 < N) {
+                *reinterpret_cast<half8v*>(dst) = v;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (n + e < N) dst[e] = v[e];
+            }
+        }
+        if (i0 + 2 < WM) {      // the next pair of fragment rows reuses the region
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    }
+}
+
 }  // namespace arcq
