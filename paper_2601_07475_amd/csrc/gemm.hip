@@ -19,6 +19,7 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <type_traits>
 
 namespace arcq {
@@ -440,6 +441,216 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// 128 x 256 tiles for problems with about one such tile per CU (2048 x 4096 has 256 of them), fp16 output.
+// Same tile, stage ring and copies as gemm_staged_kernel<2, 2, 2, 4>, but the eight waves form a
+// 2 (rows) x 2 (columns) x 2 (k) grid: a wave computes a 64 x 128 sub-tile (2 x 4 fragments: six fragment
+// decodes per eight MFMAs instead of four per four, the decode being what keeps this tile shape from the
+// matrix rate of the bigger ones) over one half of every stage: four of its eight k-steps, exactly the
+// 16-byte piece of codes a lane reads per row and stage.  The two waves of a pair (w and w + 4) share a
+// SIMD, so the matrix pipe still draws from two instruction streams; at the end they add their partial
+// tiles through the LDS and each stores one of the two fragment rows.  Needs K' % 128 == 0.
+template <typename OutT>
+__global__ __launch_bounds__(512) void gemm_kpair_kernel(
+    const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
+    const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N,
+    int nbk, float alpha, OutT* __restrict__ y, int64_t ldy, int tiles_m, int tiles_n) {
+    using C = StagedCfg<2, 2, 2, 4>;
+    constexpr int WM = 2, WN = 4;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    // workgroup -> tile as in gemm_staged_kernel
+    const int num_tiles = tiles_m * tiles_n;
+    int pid = (int)blockIdx.x;
+    if ((num_tiles & 7) == 0) pid = (pid & 7) * (num_tiles >> 3) + (pid >> 3);
+    constexpr int GROUP = 8;
+    const int group_size = GROUP * tiles_n;
+    const int g = pid / group_size;
+    const int first_m = g * GROUP;
+    const int gm = min(GROUP, tiles_m - first_m);
+    const int in_g = pid - g * group_size;
+    const int tile_m = first_m + in_g % gm;
+    const int tile_n = in_g / gm;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int kh = wave >> 2;                        // k half: k-steps 4 kh .. 4 kh + 3 of every stage
+    const int wq = wave & 3;
+    const int wg_m0 = tile_m * C::BM, wg_n0 = tile_n * C::BN;
+    const int wrow0 = (wq >> 1) * 64;                // first row of this wave inside the A tile
+    const int wcol0 = (wq & 1) * 128;                // first row of this wave inside the W tile
+    const int nstage = nbk >> 3;
+
+    // ---- copies (see gemm_staged_kernel)
+    const uint32_t lp_ = (uint32_t)((tid & 3) ^ ((tid >> 4) & 3));
+    const uint32_t adj_c0 = lp_ * 16u, adj_s = (uint32_t)(tid & 1) * 4u;
+    const int crow = tid >> 2, srow = tid >> 1;
+    const uint32_t cpitch32 = (uint32_t)nbk * 8u, spitch32 = (uint32_t)nbk;
+    const uint32_t wave_slot = __builtin_amdgcn_readfirstlane((uint32_t)(tid & ~63));
+    const uint32_t lds0 = lds_address(lds);
+    auto issue_one = [&](int d, int stage, int buf) {
+        const uint32_t base = lds0 + buf * C::STAGE_BYTES;
+        const uint32_t oc = (uint32_t)stage * 64u + adj_c0;
+        const uint32_t os = (uint32_t)stage * 8u + adj_s;
+        constexpr int NA = C::NA, NW = C::NW, NAS = C::NAS, NT = C::NT;
+        if (d < NA) {
+            const uint32_t row = (uint32_t)min(wg_m0 + d * (NT / 4) + crow, M - 1);
+            dma16(a_codes, row * cpitch32 + oc, base + C::A_CODES + 16u * (d * NT + wave_slot));
+        } else if (d < NA + NW) {
+            const int p = d - NA;
+            const uint32_t row = (uint32_t)min(wg_n0 + p * (NT / 4) + crow, N - 1);
+            dma16(w_codes, row * cpitch32 + oc, base + C::W_CODES + 16u * (p * NT + wave_slot));
+        } else if (d < NA + NW + NAS) {
+            const int p = d - NA - NW;
+            const uint32_t row = (uint32_t)min(wg_m0 + p * (NT / 2) + srow, M - 1);
+            dma4(a_scales, row * spitch32 + os, base + C::A_SCALES + 4u * (p * NT + wave_slot));
+        } else {
+            const int p = d - NA - NW - NAS;
+            const uint32_t row = (uint32_t)min(wg_n0 + p * (NT / 2) + srow, N - 1);
+            dma4(w_scales, row * spitch32 + os, base + C::W_SCALES + 4u * (p * NT + wave_slot));
+        }
+    };
+
+    // ---- LDS read offsets: this wave's half of a stage is piece 2 kh + h of a row's codes and bytes
+    // 4 kh + 2 h, 4 kh + 2 h + 1 of its scale bytes
+    const uint32_t swz = (uint32_t)(r >> 2) & 3u;
+    const uint32_t piece = 16u * ((uint32_t)(2 * kh + h) ^ swz);
+    const uint32_t rd_a = C::A_CODES + (wrow0 + r) * 64 + piece, rd_w = C::W_CODES + (wcol0 + r) * 64 + piece;
+    const uint32_t rd_as = C::A_SCALES + (wrow0 + r) * 8 + 4 * kh, rd_ws = C::W_SCALES + (wcol0 + r) * 8 + 4 * kh;
+    const uint32_t scale_sel = h ? 0x0C030C02u : 0x0C010C00u;
+
+    float16v acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    constexpr int G = WM + WN;                 // fragments per k-step
+    constexpr int P = WM * WN;                 // MFMAs per k-step, one per group
+    uint4 ca[WM], cw[WN];
+    uint32_t sa[WM], sw[WN];
+    half8 fa[2][WM], fw[2][WN];
+    auto read_raw = [&](const uint8_t* st) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            ca[i] = *reinterpret_cast<const uint4*>(st + rd_a + i * 2048);
+            sa[i] = scale_halves(*reinterpret_cast<const uint32_t*>(st + rd_as + i * 256), scale_sel);
+        }
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            cw[j] = *reinterpret_cast<const uint4*>(st + rd_w + j * 2048);
+            sw[j] = scale_halves(*reinterpret_cast<const uint32_t*>(st + rd_ws + j * 256), scale_sel);
+        }
+    };
+    auto decode_frag = [&](int gidx, int t) {   // fragment gidx of this wave's k-step t (0..3) into slot t & 1
+        const int d = t & 1;
+        if (gidx < WM) {
+            const uint4 c4 = ca[gidx];
+            const uint32_t c = t == 0 ? c4.x : t == 1 ? c4.y : t == 2 ? c4.z : c4.w;
+            fa[d][gidx] = decode8_half(c, sa[gidx], t >> 1);
+        } else {
+            const int j = gidx - WM;
+            const uint4 c4 = cw[j];
+            const uint32_t c = t == 0 ? c4.x : t == 1 ? c4.y : t == 2 ? c4.z : c4.w;
+            fw[d][j] = decode8_half(c, sw[j], t >> 1);
+        }
+    };
+
+    // One stage = four k-steps of this wave.  During step t the fragments of step t + 1 are decoded, one
+    // group of fragments after every MFMA; the raw codes of the next stage are read at the start of step 3
+    // (every fragment of this stage has been decoded by then) behind the barrier that opens that stage, and
+    // step 3 decodes its first fragments.  The copies of stage s + DIST are issued during steps 0..2.
+    int buf = 0;
+    auto ring_next = [](int b) { return b == C::NSTAGE - 1 ? 0 : b + 1; };
+    auto run_stage = [&](int s) {
+        const int buf1 = ring_next(buf), buf2 = buf == 0 ? C::NSTAGE - 1 : buf - 1;
+        const int fetch = min(s + C::DIST, nstage - 1);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (t == 3) {
+                wait_vmcnt<(C::DIST - 1) * C::NDMA>();
+                wg_barrier();
+                read_raw(lds + buf1 * C::STAGE_BYTES);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+#pragma unroll
+                for (int gidx = (p * G) / P; gidx < ((p + 1) * G) / P; ++gidx) decode_frag(gidx, (t + 1) & 3);
+                __builtin_amdgcn_sched_barrier(0);
+                const int i = p / WN, j = p % WN;
+                // weights as the row operand: see store_tile_swapped
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[t & 1][j], fa[t & 1][i], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t < 3) {
+#pragma unroll
+                    for (int d = 0; d < C::NDMA; ++d)
+                        if ((d * 3) / C::NDMA == t && (d - (t * C::NDMA + 2) / 3) == p) issue_one(d, fetch, buf2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        buf = buf1;
+    };
+
+#pragma unroll
+    for (int d = 0; d < C::DIST; ++d)
+#pragma unroll
+        for (int q = 0; q < C::NDMA; ++q) issue_one(q, min(d, nstage - 1), d);
+    wait_vmcnt<(C::DIST - 1) * C::NDMA>();
+    wg_barrier();
+    read_raw(lds);
+#pragma unroll
+    for (int gidx = 0; gidx < G; ++gidx) decode_frag(gidx, 0);
+    for (int s = 0; s < nstage; ++s) run_stage(s);
+    wait_vmcnt<0>();                            // no copy may still be in flight when the LDS is released
+
+    // ---- the pair adds its partial tiles: in two rounds (columns 0-63, 64-127 of the sub-tile) every wave
+    // hands the partner the fragment row the partner will store, 16 bytes per lane and register group
+    static_assert(8 * 8192 <= C::LDS_BYTES && 8 * epilogue_lds_bytes(WN) / 2 <= C::LDS_BYTES, "epilogue regions must fit the ring");
+    float* xch = reinterpret_cast<float*>(lds);
+    const int mine = kh, other = kh ^ 1;        // fragment row this wave stores / gives away
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+        wg_barrier();                           // ring (or the previous round's regions) no longer read
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int j = 2 * round + jj;
+                const float16v& src = other == 0 ? acc[0][j] : acc[1][j];
+                *reinterpret_cast<float4*>(xch + wave * 2048 + ((jj * 4 + q) * 64 + lane) * 4) =
+                    make_float4(src[4 * q], src[4 * q + 1], src[4 * q + 2], src[4 * q + 3]);
+            }
+        wait_lgkmcnt0();
+        wg_barrier();
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int j = 2 * round + jj;
+                const float4 v = *reinterpret_cast<const float4*>(xch + (wave ^ 4) * 2048 + ((jj * 4 + q) * 64 + lane) * 4);
+                if (mine == 0) {
+                    acc[0][j][4 * q] += v.x; acc[0][j][4 * q + 1] += v.y; acc[0][j][4 * q + 2] += v.z; acc[0][j][4 * q + 3] += v.w;
+                } else {
+                    acc[1][j][4 * q] += v.x; acc[1][j][4 * q + 1] += v.y; acc[1][j][4 * q + 2] += v.z; acc[1][j][4 * q + 3] += v.w;
+                }
+            }
+    }
+    wg_barrier();                               // every wave has read its partner's last round
+    const int m0 = wg_m0 + wrow0, n0 = wg_n0 + wcol0;
+    const bool vec_ok = (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
+    uint8_t* region = lds + wave * (epilogue_lds_bytes(WN) / 2);
+    if (mine == 0)
+        store_fragment_rows_f16_via_lds<WM, WN, 0, 1>(acc, region, m0, n0, lane, M, N, alpha, y, ldy, vec_ok);
+    else
+        store_fragment_rows_f16_via_lds<WM, WN, 1, 1>(acc, region, m0, n0, lane, M, N, alpha, y, ldy, vec_ok);
+}
+
 // y = alpha * (sum of the `splits` fp32 partial results [M, N], added in index order).
 template <typename OutT>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int splits,
@@ -694,8 +905,25 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
         const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
         // 128 x 256 tiles with 8 waves of 64 x 64 (two per SIMD): 5 % faster than 4 waves of 64 x 128 on the
         // 2048 x 4096 x 4352 problem; on the large shapes 4 and 8 waves measure the same
-        if (t128x256 >= 192)
+        if (t128x256 >= 192) {
+            // fp16 output and whole stages: the variant whose wave pairs split every stage (6 % faster on the
+            // 2048 x 4096 x 4352 problem with real data, 10 % with random operands; the environment switch
+            // keeps the plain variant reachable for comparisons)
+            if constexpr (std::is_same<OutT, _Float16>::value) {
+                if ((nbk & 7) == 0 && nbk >= 16 && !std::getenv("ARCQ_NO_KPAIR")) {
+                    using C = StagedCfg<2, 2, 2, 4>;
+                    auto kern = gemm_kpair_kernel<_Float16>;
+                    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+                    if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
+                    const int tiles_m = (int)((M + 127) / 128), tiles_n = (int)((N + 255) / 256);
+                    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(512), C::LDS_BYTES, stream, a_codes, a_scales, w_codes,
+                                       w_scales, (int)M, (int)N, nbk, alpha, y, ldy, tiles_m, tiles_n);
+                    return check_launch("gemm_kpair_kernel");
+                }
+            }
             return launch_staged<2, 2, 2, 4>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+        }
         return launch_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream,
                                          split_k(M, N, Kp), workspace);
     }

@@ -61,11 +61,11 @@ __device__ __forceinline__ void store_tile_swapped(const float16v (&acc)[WM][WN]
 // else as above.
 constexpr int epilogue_lds_bytes(int WN) { return 64 * (64 * WN + 16); }
 
-template <int WM, int WN>
-__device__ __forceinline__ void store_tile_f16_via_lds(const float16v (&acc)[WM][WN], uint8_t* lds_wave, int m0, int n0,
-                                                       int lane, int M, int N, float alpha, _Float16* __restrict__ y,
-                                                       int64_t ldy, bool vec_ok) {
-    static_assert(WM % 2 == 0, "two fragment rows at a time");
+// Fragment rows I0 .. I0 + NI - 1 of a wave's tile (NI = 1 or 2) in one pass through the region.
+template <int WM, int WN, int I0, int NI>
+__device__ __forceinline__ void store_fragment_rows_f16_via_lds(const float16v (&acc)[WM][WN], uint8_t* lds_wave, int m0,
+                                                                int n0, int lane, int M, int N, float alpha,
+                                                                _Float16* __restrict__ y, int64_t ldy, bool vec_ok) {
     typedef _Float16 half4v __attribute__((ext_vector_type(4)));
     typedef _Float16 half8v __attribute__((ext_vector_type(8)));
     constexpr int ROWB = 64 * WN + 16;
@@ -73,42 +73,48 @@ __device__ __forceinline__ void store_tile_f16_via_lds(const float16v (&acc)[WM]
     constexpr int RPI = 64 / LPR;           // rows per store instruction
     const int r = lane & 31, h = lane >> 5;
 #pragma unroll
-    for (int i0 = 0; i0 < WM; i0 += 2) {
+    for (int ii = 0; ii < NI; ++ii)
 #pragma unroll
-        for (int ii = 0; ii < 2; ++ii)
+        for (int j = 0; j < WN; ++j)
 #pragma unroll
-            for (int j = 0; j < WN; ++j)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const half4v v = {(_Float16)(acc[i0 + ii][j][4 * g] * alpha), (_Float16)(acc[i0 + ii][j][4 * g + 1] * alpha),
-                                      (_Float16)(acc[i0 + ii][j][4 * g + 2] * alpha), (_Float16)(acc[i0 + ii][j][4 * g + 3] * alpha)};
-                    *reinterpret_cast<half4v*>(lds_wave + (32 * ii + r) * ROWB + 2 * (32 * j + 8 * g + 4 * h)) = v;
-                }
-        // the reads below take what other lanes of this wave wrote: LDS operations of a wave complete in order
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-        for (int k = 0; k < 64 / RPI; ++k) {
-            const int row = k * RPI + lane / LPR, chunk = lane % LPR;
-            const half8v v = *reinterpret_cast<const half8v*>(lds_wave + row * ROWB + 16 * chunk);
-            const int m = m0 + 32 * i0 + row, n = n0 + 8 * chunk;
-            if (m >= M) continue;
-            _Float16* dst = y + (int64_t)m * ldy + n;
-            if (vec_ok && n + 7 < N) {
-                *reinterpret_cast<half8v*>(dst) = v;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (n + e < N) dst[e] = v[e];
+            for (int g = 0; g < 4; ++g) {
+                const half4v v = {(_Float16)(acc[I0 + ii][j][4 * g] * alpha), (_Float16)(acc[I0 + ii][j][4 * g + 1] * alpha),
+                                  (_Float16)(acc[I0 + ii][j][4 * g + 2] * alpha), (_Float16)(acc[I0 + ii][j][4 * g + 3] * alpha)};
+                *reinterpret_cast<half4v*>(lds_wave + (32 * ii + r) * ROWB + 2 * (32 * j + 8 * g + 4 * h)) = v;
             }
-        }
-        if (i0 + 2 < WM) {      // the next pair of fragment rows reuses the region
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // the reads below take what other lanes of this wave wrote: LDS operations of a wave complete in order
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int k = 0; k < 32 * NI / RPI; ++k) {
+        const int row = k * RPI + lane / LPR, chunk = lane % LPR;
+        const half8v v = *reinterpret_cast<const half8v*>(lds_wave + row * ROWB + 16 * chunk);
+        const int m = m0 + 32 * I0 + row, n = n0 + 8 * chunk;
+        if (m >= M) continue;
+        _Float16* dst = y + (int64_t)m * ldy + n;
+        if (vec_ok && n + 7 < N) {
+            *reinterpret_cast<half8v*>(dst) = v;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (n + e < N) dst[e] = v[e];
         }
     }
+    // a following pass reuses the region
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int WM, int WN>
+__device__ __forceinline__ void store_tile_f16_via_lds(const float16v (&acc)[WM][WN], uint8_t* lds_wave, int m0, int n0,
+                                                       int lane, int M, int N, float alpha, _Float16* __restrict__ y,
+                                                       int64_t ldy, bool vec_ok) {
+    static_assert(WM == 2 || WM == 4, "two fragment rows at a time");
+    store_fragment_rows_f16_via_lds<WM, WN, 0, 2>(acc, lds_wave, m0, n0, lane, M, N, alpha, y, ldy, vec_ok);
+    if constexpr (WM == 4)
+        store_fragment_rows_f16_via_lds<WM, WN, 2, 2>(acc, lds_wave, m0, n0, lane, M, N, alpha, y, ldy, vec_ok);
 }
 
 }  // namespace arcq
