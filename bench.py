@@ -42,11 +42,11 @@ PEAK_MFMA_FP4_TFLOPS = 10100.0 # MI355X dense fp4 MFMA (the MXFP4 variant's GEMM
 # profiles/), scaled by the factor the same counters read for a plain copy of known size.
 # workload -> kernel -> bytes; None where not measured.
 MEASURED_TRAFFIC = {
-    "c2_llama8b_q": {"arcq_gemm": 57313280, "arcq_quantize_act": 22005760, "arcq_rmsnorm_quantize_act": 22118400, "arcq_mx_quantize_act": 21751808, "arcq_mx_gemm": 55400448},
-    "c4_qwen32b_mlp": {"arcq_gemm": 779610112, "arcq_quantize_act": 55155712, "arcq_rmsnorm_quantize_act": 55266304, "arcq_mx_quantize_act": 54495232, "arcq_mx_gemm": 735872000},
-    "c5_llama70b_down": {"arcq_gemm": 1821454336, "arcq_quantize_act": 621324288, "arcq_rmsnorm_quantize_act": 636157952, "arcq_mx_quantize_act": 599992320, "arcq_mx_gemm": 1718959104},
-    "c3a_llama8b_up": {"arcq_gemm": 36096000, "arcq_quantize_act": 350208, "arcq_rmsnorm_quantize_act": 464896, "arcq_mx_quantize_act": 358400, "arcq_mx_gemm": 34027520},
-    "c3b_llama8b_down": {"arcq_gemm": 35072000, "arcq_quantize_act": 1097728, "arcq_rmsnorm_quantize_act": 1376256, "arcq_mx_quantize_act": 1101824, "arcq_mx_gemm": 33011712},
+    "c2_llama8b_q": {"arcq_gemm": 57349301, "arcq_quantize_act": 22007018, "arcq_rmsnorm_quantize_act": 22120448, "arcq_mx_quantize_act": 21762284, "arcq_mx_gemm": 54877499},
+    "c4_qwen32b_mlp": {"arcq_gemm": 779807805, "arcq_quantize_act": 55148168, "arcq_rmsnorm_quantize_act": 55268075, "arcq_mx_quantize_act": 54505236, "arcq_mx_gemm": 735334209},
+    "c5_llama70b_down": {"arcq_gemm": 1782073920, "arcq_quantize_act": 621416472, "arcq_rmsnorm_quantize_act": 632529053, "arcq_mx_quantize_act": 612827975, "arcq_mx_gemm": 1694876260},
+    "c3a_llama8b_up": {"arcq_gemm": 36081358, "arcq_quantize_act": 353792, "arcq_rmsnorm_quantize_act": 467456, "arcq_mx_quantize_act": 369152, "arcq_mx_gemm": 33942992},
+    "c3b_llama8b_down": {"arcq_gemm": 35049944, "arcq_quantize_act": 1101312, "arcq_rmsnorm_quantize_act": 1378816, "arcq_mx_quantize_act": 1111552, "arcq_mx_gemm": 32982852},
 }
 
 
