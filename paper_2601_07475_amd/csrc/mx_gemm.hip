@@ -296,7 +296,21 @@ __global__ __launch_bounds__(256) void mx_gemm_direct_kernel(
 // into registers; latency is hidden by occupancy.
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-template <int MT, int NT, int WAVES, int U, typename OutT>
+// GRP: whole chunks are taken four at a time (512 k) with the scale bytes of the four chunks fetched by ONE
+// four-byte load per lane: the four lanes of a row read 16 contiguous bytes, and a 4 x 4 byte transpose
+// across the four lane groups (two lane-swap instructions and two byte permutes with per-lane selectors)
+// leaves every lane with the scale bytes of its block for the four chunks, which the matrix instruction
+// picks with its byte selector.  The address unit of a CU spends about two cycles per (row, 64-byte
+// segment) an instruction touches, so a four-byte scale load per chunk costs as much as the code load.
+typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t transpose_scale_bytes(uint32_t s, uint32_t sel_half, uint32_t sel_byte) {
+    const uint2v x = __builtin_amdgcn_permlane32_swap(s, s, false, false);     // (q, q ^ 2): own and partner word
+    const uint32_t pair = __builtin_amdgcn_perm(x[1], x[0], sel_half);         // bytes {0,1} or {2,3} of chunks (q & 1), (q & 1) + 2
+    const uint2v t = __builtin_amdgcn_permlane16_swap(pair, pair, false, false);   // (q, q ^ 1)
+    return __builtin_amdgcn_perm(t[1], t[0], sel_byte);                        // byte q of chunks 0, 1, 2, 3
+}
+
+template <int MT, int NT, int WAVES, int U, bool GRP, typename OutT>
 __global__ __launch_bounds__(WAVES * 64) void mx_gemm_skinny_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N, int nb,
@@ -329,7 +343,51 @@ __global__ __launch_bounds__(WAVES * 64) void mx_gemm_skinny_kernel(
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    for (int c0 = wave * U; c0 < nchunk; c0 += WAVES * U) {
+    int cbase = 0, first_wave = 0;              // first chunk and first wave of the chunk-at-a-time loop
+    if constexpr (GRP) {
+        const int ngroup = nchunk >> 2;         // groups of four chunks
+        const uint32_t sel_half = q < 2 ? 0x05040100u : 0x07060302u;
+        const uint32_t sel_byte = (q & 1) ? 0x07030501u : 0x06020400u;
+        for (int g = wave; g < ngroup; g += WAVES) {
+            uint4 ca[4][MT], cw[4][NT];
+            uint32_t sa[MT], sw[NT];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+#pragma unroll
+                for (int r = 0; r < MT; ++r) ca[m][r] = *reinterpret_cast<const uint4*>(ac[r] + 256 * (int64_t)g + 64 * m);
+#pragma unroll
+                for (int t = 0; t < NT; ++t) cw[m][t] = *reinterpret_cast<const uint4*>(wc[t] + 256 * (int64_t)g + 64 * m);
+            }
+#pragma unroll
+            for (int r = 0; r < MT; ++r) sa[r] = *reinterpret_cast<const uint32_t*>(as[r] + 16 * (int64_t)g + 4 * q);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) sw[t] = *reinterpret_cast<const uint32_t*>(ws[t] + 16 * (int64_t)g + 4 * q);
+#pragma unroll
+            for (int r = 0; r < MT; ++r) sa[r] = transpose_scale_bytes(sa[r], sel_half, sel_byte);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) sw[t] = transpose_scale_bytes(sw[t], sel_half, sel_byte);
+            auto step = [&](auto mtag) {
+                constexpr int m = decltype(mtag)::value;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int8v vw = {(int)cw[m][t].x, (int)cw[m][t].y, (int)cw[m][t].z, (int)cw[m][t].w, 0, 0, 0, 0};
+#pragma unroll
+                    for (int r = 0; r < MT; ++r) {
+                        const int8v va = {(int)ca[m][r].x, (int)ca[m][r].y, (int)ca[m][r].z, (int)ca[m][r].w, 0, 0, 0, 0};
+                        // byte m of the scale registers belongs to chunk m
+                        acc[r][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(va, vw, acc[r][t], 4, 4, m, (int)sa[r], m, (int)sw[t]);
+                    }
+                }
+            };
+            step(std::integral_constant<int, 0>{});
+            step(std::integral_constant<int, 1>{});
+            step(std::integral_constant<int, 2>{});
+            step(std::integral_constant<int, 3>{});
+        }
+        cbase = 4 * ngroup;
+        first_wave = ngroup % WAVES;            // the waves that took one group less come first
+    }
+    for (int c0 = cbase + ((wave - first_wave + WAVES) % WAVES) * U; c0 < nchunk; c0 += WAVES * U) {
         uint4 ca[U][MT], cw[U][NT];
         uint32_t sa[U][MT], sw[U][NT];
 #pragma unroll
@@ -385,7 +443,7 @@ __global__ __launch_bounds__(WAVES * 64) void mx_gemm_skinny_kernel(
 template <int MT, int NT, int WAVES, int U, typename OutT>
 arcq_status launch_mx_skinny(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                              const uint8_t* w_scales, int M, int N, int nb, OutT* y, int64_t ldy, hipStream_t stream) {
-    hipLaunchKernelGGL((mx_gemm_skinny_kernel<MT, NT, WAVES, U, OutT>), dim3((N + 16 * NT - 1) / (16 * NT)),
+    hipLaunchKernelGGL((mx_gemm_skinny_kernel<MT, NT, WAVES, U, (MT <= 4), OutT>), dim3((N + 16 * NT - 1) / (16 * NT)),
                        dim3(WAVES * 64), 0, stream, a_codes, a_scales, w_codes, w_scales, M, N, nb, y, ldy);
     return check_launch("mx_gemm_skinny_kernel");
 }
