@@ -616,6 +616,7 @@ __global__ __launch_bounds__(512) void gemm_kpair_kernel(
     const int mine = kh, other = kh ^ 1;        // fragment row this wave stores / gives away
 #pragma unroll
     for (int round = 0; round < 2; ++round) {
+        wait_lgkmcnt0();                        // this wave's reads of the ring / of the previous round have returned
         wg_barrier();                           // ring (or the previous round's regions) no longer read
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
@@ -641,6 +642,7 @@ __global__ __launch_bounds__(512) void gemm_kpair_kernel(
                 }
             }
     }
+    wait_lgkmcnt0();
     wg_barrier();                               // every wave has read its partner's last round
     const int m0 = wg_m0 + wrow0, n0 = wg_n0 + wcol0;
     const bool vec_ok = (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
