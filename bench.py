@@ -42,11 +42,11 @@ PEAK_MFMA_FP4_TFLOPS = 10100.0 # MI355X dense fp4 MFMA (the MXFP4 variant's GEMM
 # profiles/), scaled by the factor the same counters read for a plain copy of known size.
 # workload -> kernel -> bytes; None where not measured.
 MEASURED_TRAFFIC = {
-    "c2_llama8b_q": {"arcq_gemm": 57349301, "arcq_quantize_act": 22007018, "arcq_rmsnorm_quantize_act": 22120448, "arcq_mx_quantize_act": 21762284, "arcq_mx_gemm": 54877499},
-    "c4_qwen32b_mlp": {"arcq_gemm": 779807805, "arcq_quantize_act": 55148168, "arcq_rmsnorm_quantize_act": 55268075, "arcq_mx_quantize_act": 54505236, "arcq_mx_gemm": 735334209},
-    "c5_llama70b_down": {"arcq_gemm": 1782073920, "arcq_quantize_act": 621416472, "arcq_rmsnorm_quantize_act": 632529053, "arcq_mx_quantize_act": 612827975, "arcq_mx_gemm": 1694876260},
-    "c3a_llama8b_up": {"arcq_gemm": 36081358, "arcq_quantize_act": 353792, "arcq_rmsnorm_quantize_act": 467456, "arcq_mx_quantize_act": 369152, "arcq_mx_gemm": 33942992},
-    "c3b_llama8b_down": {"arcq_gemm": 35049944, "arcq_quantize_act": 1101312, "arcq_rmsnorm_quantize_act": 1378816, "arcq_mx_quantize_act": 1111552, "arcq_mx_gemm": 32982852},
+    "c2_llama8b_q": {"arcq_gemm": 57349504, "arcq_quantize_act": 22006965, "arcq_rmsnorm_quantize_act": 22120448, "arcq_mx_quantize_act": 21762180, "arcq_mx_gemm": 54881595},
+    "c4_qwen32b_mlp": {"arcq_gemm": 779851793, "arcq_quantize_act": 55148144, "arcq_rmsnorm_quantize_act": 55268260, "arcq_mx_quantize_act": 54505698, "arcq_mx_gemm": 735399787},
+    "c5_llama70b_down": {"arcq_gemm": 1782143904, "arcq_quantize_act": 621370874, "arcq_rmsnorm_quantize_act": 632534163, "arcq_mx_quantize_act": 612731202, "arcq_mx_gemm": 1694879065},
+    "c3a_llama8b_up": {"arcq_gemm": 36259724, "arcq_quantize_act": 353792, "arcq_rmsnorm_quantize_act": 467456, "arcq_mx_quantize_act": 369152, "arcq_mx_gemm": 34065589},
+    "c3b_llama8b_down": {"arcq_gemm": 35084385, "arcq_quantize_act": 1101312, "arcq_rmsnorm_quantize_act": 1378816, "arcq_mx_quantize_act": 1111552, "arcq_mx_gemm": 32979164},
 }
 
 
