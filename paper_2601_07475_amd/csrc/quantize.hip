@@ -117,7 +117,12 @@ void quantize_rows_kernel(
     // Lanes past the last block of a row (only when K/16 is not a multiple of the workgroup
     // size) repeat the last block: same values stored to the same addresses, no divergence.
     int blk[BPT];
-    uint32_t off[BPT][16];                  // LDS byte offsets of this lane's channels
+    // LDS byte offsets of this lane's channels; the variant that also keeps gamma in registers packs them as
+    // 16-bit channel indices, two per register (it would spill otherwise: 128 registers per lane is all a
+    // workgroup of more than 512 lanes can have), and unpacks with one instruction per use
+    constexpr bool PACK = NORM == 2;
+    uint32_t off[PACK ? 1 : BPT][16];
+    uint32_t chp[PACK ? BPT : 1][8];
 #pragma unroll
     for (int j = 0; j < BPT; ++j) {
         blk[j] = min(tid + j * T, nb - 1);
@@ -125,12 +130,26 @@ void quantize_rows_kernel(
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int4 v4 = pp[q];
-            off[j][4 * q + 0] = 2u * (uint32_t)v4.x;
-            off[j][4 * q + 1] = 2u * (uint32_t)v4.y;
-            off[j][4 * q + 2] = 2u * (uint32_t)v4.z;
-            off[j][4 * q + 3] = 2u * (uint32_t)v4.w;
+            if constexpr (PACK) {
+                chp[j][2 * q] = (uint32_t)v4.x | ((uint32_t)v4.y << 16);
+                chp[j][2 * q + 1] = (uint32_t)v4.z | ((uint32_t)v4.w << 16);
+            } else {
+                off[j][4 * q + 0] = 2u * (uint32_t)v4.x;
+                off[j][4 * q + 1] = 2u * (uint32_t)v4.y;
+                off[j][4 * q + 2] = 2u * (uint32_t)v4.z;
+                off[j][4 * q + 3] = 2u * (uint32_t)v4.w;
+            }
         }
     }
+    auto off_of = [&](int j, int i) -> uint32_t {
+        if constexpr (PACK) {
+            uint32_t c = chp[j][i >> 1];
+            asm volatile("" : "+v"(c));          // keeps the unpacking inside the row loop (hoisted, it is 32 registers again)
+            return (i & 1) ? (c >> 15) & 0x1FFFEu : (c & 0xFFFFu) << 1;
+        } else {
+            return off[j][i];
+        }
+    };
 
     // NORM: gamma of this lane's channels, fixed for every row
     constexpr bool GAMMA_REGS = NORM == 2;      // fp16, two per register
@@ -148,7 +167,7 @@ void quantize_rows_kernel(
 #pragma unroll
         for (int j = 0; j < BPT; ++j)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) gam[j][i] = g16(off[j][2 * i]) | (g16(off[j][2 * i + 1]) << 16);
+            for (int i = 0; i < 8; ++i) gam[j][i] = g16(off_of(j, 2 * i)) | (g16(off_of(j, 2 * i + 1)) << 16);
     }
     // LDS byte address of the statistics words behind the row buffers:
     // +0, +8, +16 integer sums of the exact path; +24 its rstd; +32, +40 fp64 sums of the fast path
@@ -229,7 +248,7 @@ void quantize_rows_kernel(
                     double p_aa = 0.0, p_ab = 0.0, p_bb = 0.0;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const __half h = *reinterpret_cast<const __half*>(lds_row + base + off[j][i]);
+                        const __half h = *reinterpret_cast<const __half*>(lds_row + base + off_of(j, i));
                         const float s16 = fabsf(__half2float(h)) * 16.0f;   // exact, < 2^20, a multiple of 2^-20
                         const float fa = truncf(s16);
                         const float fb = (s16 - fa) * 0x1p20f;              // exact
@@ -289,7 +308,7 @@ void quantize_rows_kernel(
             float v[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const __half h = *reinterpret_cast<const __half*>(lds_row + base + off[j][i]);
+                const __half h = *reinterpret_cast<const __half*>(lds_row + base + off_of(j, i));
                 if (NORM) {
                     // t = fl16(fl32(x * rstd)): two roundings, as the reference layer does it.  The product is
                     // pinned to a register between them; left alone the compiler fuses multiply and conversion
@@ -300,7 +319,7 @@ void quantize_rows_kernel(
                     const __half t16 = __float2half_rn(prod);
                     const __half g = GAMMA_REGS
                         ? __ushort_as_half((unsigned short)((gam[j][i >> 1] >> (16 * (i & 1))) & 0xFFFFu))
-                        : *reinterpret_cast<const __half*>(lds_gamma + off[j][i]);
+                        : *reinterpret_cast<const __half*>(lds_gamma + off_of(j, i));
                     // fp16 times fp16 rounded once to fp16
                     v[i] = __half2float(__hmul(t16, g));
                 } else {
