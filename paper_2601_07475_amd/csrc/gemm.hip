@@ -316,12 +316,12 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    // ---- per-stage compute, software-pipelined by hand (one wave per SIMD: nothing else hides
-    // a stall, so every wait is placed where its data has long been ready).
+    // ---- per-stage compute, software-pipelined by hand (with one or two waves per SIMD little else
+    // hides a stall, so every wait is placed where its data has long been ready).
     // A k-step (one block, 16 k) is WM*WN MFMAs fed by WM + WN fragments of 8 fp16 per lane.
-    // While the MFMAs of step x run, the fragments of step x+1 are decoded: after every pair of
-    // MFMAs the decode of one (or two) fragments is placed, and scheduling barriers keep the
-    // compiler from regrouping them, so the matrix pipe stays busy while the vector ALU decodes.
+    // While the MFMAs of step x run, the fragments of step x+1 are decoded: after every group of
+    // MFMAs (see MPG) the decode of its share of the fragments is placed, and scheduling barriers keep
+    // the compiler from regrouping them, so the matrix pipe stays busy while the vector ALU decodes.
     // The pipeline runs ACROSS stages: the barrier that opens stage s+1 sits before step 6 of
     // stage s; step 6 reads the first raw codes of stage s+1 from LDS and step 7 decodes its
     // first fragments.  The copies for stage s + NSTAGE - 1 are issued two per k-step during steps 0-5 of
@@ -329,9 +329,9 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     // that opened stage s), so no wave ever queues a burst of memory instructions.
     constexpr int G = WM + WN;                 // fragments per k-step
     // MFMAs per group: after every group the decode of G / P fragments is placed.  With few MFMAs per
-    // fragment (2 x 2 fragments: ten vector instructions per MFMA) single MFMAs interleave best with the
+    // fragment (2 x 2 fragments: nine vector instructions per MFMA) single MFMAs interleave best with the
     // vector work (a register-only model of this loop ran 10 % faster with singles than with pairs);
-    // with 4 x 4 fragments pairs and singles measure the same.
+    // with 4 x 4 fragments pairs and singles measure the same in that model, and singles spill here.
     constexpr int MPG = (WM * WN >= 16) ? 2 : 1;
     constexpr int P = (WM * WN) / MPG;         // groups per k-step
     uint4 ca[2][WM], cw[2][WN];
