@@ -313,6 +313,28 @@ def test_gemm_extreme_scales_and_codes():
     assert np.array_equal(Y.cpu().numpy().astype(np.float64), Yref)
 
 
+@pytest.mark.parametrize("M,N,Kp,dtype", [
+    (300, 260, 256, torch.float32),       # 128 x 128 tiles
+    (2048, 3072, 256, torch.float32),     # 128 x 256 tiles, eight waves of 64 x 64
+    (2048, 3072, 256, torch.float16),     # 128 x 256 tiles, wave pairs splitting every stage
+    (4096, 4096, 128, torch.float16),     # 256 x 256 tiles
+])
+def test_gemm_extreme_scales_tiled_kernels(M, N, Kp, dtype):
+    """Every scale byte class (zero, subnormal, smallest and largest normal) and every code value through the
+    decode of the tiled kernels; the weights' scales are kept small so that the fp16 output stays finite."""
+    say(f"tiled gemm with extreme scale bytes M={M} N={N} K'={Kp} {dtype}")
+    rng = np.random.default_rng(23)
+    ac = rng.integers(0, 256, (M, Kp // 2), dtype=np.uint8)
+    wc = rng.integers(0, 256, (N, Kp // 2), dtype=np.uint8)
+    asc = rng.choice(np.array([0, 1, 7, 8, 9, 0x38, 0x77, 0x7D, 0x7E], dtype=np.uint8), (M, Kp // 16))
+    wsc = rng.choice(np.array([0, 1, 2, 7, 8, 9, 0x10], dtype=np.uint8), (N, Kp // 16))
+    Y = B.arcq_gemm(dev(ac), dev(asc), 1.0, dev(wc), dev(wsc), 1.0, out_dtype=dtype).float().cpu().numpy()
+    assert np.all(np.isfinite(Y))
+    rows = rng.choice(M, 64, replace=False)
+    Yref = A.gemm(ac[rows], asc[rows], np.float32(1.0), wc, wsc, np.float32(1.0))
+    assert norm_err(Y[rows], Yref) <= (GEMM_TOL_F32 if dtype == torch.float32 else GEMM_TOL_F16)
+
+
 def test_gemm_strided_output_and_guard():
     say("gemm with ldy > N")
     c = rand_case(70, 256, 90, 32, seed=31)
