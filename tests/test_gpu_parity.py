@@ -564,6 +564,26 @@ def test_mx_gemm_extreme_scales():
     assert norm_err(out[:, :N], Yref) <= GEMM_TOL_F32 and np.all(out[:, N:] == 7.0)
 
 
+@pytest.mark.parametrize("M,N,Kp,dtype", [
+    (300, 260, 512, torch.float32),       # 128 x 128 tiles
+    (2048, 3072, 384, torch.float16),     # 128 x 256 tiles, a half unit at the end
+    (4096, 4096, 256, torch.float16),     # 256 x 256 tiles
+    (64, 4100, 1280, torch.float16),      # weight-streaming kernel: two groups of four chunks and two single chunks
+])
+def test_mx_gemm_extreme_scales_every_kernel(M, N, Kp, dtype):
+    say(f"mx_gemm with extreme scale bytes M={M} N={N} K'={Kp} {dtype}")
+    rng = np.random.default_rng(29)
+    ac = rng.integers(0, 256, (M, Kp // 2), dtype=np.uint8)
+    wc = rng.integers(0, 256, (N, Kp // 2), dtype=np.uint8)
+    asc = rng.choice(np.array([101, 102, 127, 139, 140], np.uint8), (M, Kp // 32))
+    wsc = rng.choice(np.array([101, 110, 118, 120], np.uint8), (N, Kp // 32))       # small, so fp16 outputs stay finite
+    Y = B.arcq_mx_gemm(dev(ac), dev(asc), dev(wc), dev(wsc), out_dtype=dtype).float().cpu().numpy()
+    assert np.all(np.isfinite(Y))
+    rows = rng.choice(M, min(M, 64), replace=False)
+    Yref = MX.gemm(ac[rows], asc[rows], wc, wsc)
+    assert norm_err(Y[rows], Yref) <= (GEMM_TOL_F32 if dtype == torch.float32 else GEMM_TOL_F16)
+
+
 def test_mx_full_size_llama8b_qproj():
     """The bench's MXFP4 workload at full size: quantizer bit-exact, GEMM on sampled rows."""
     say("mx path full size 2048 x 4096 x 4096, S = 256")
