@@ -154,7 +154,7 @@ arcq_status arcq_gemm_workspace_size(int64_t M, int64_t N, int64_t Kp, size_t* b
  * a_*  packed activations [M, Kp] from arcq_quantize_act;  w_*  packed weights [N, Kp]
  *      from arcq_pack_weight; codes 8-byte aligned.  Kp % 16 == 0, Kp > 0.
  * y    out [M, N] row-major, pitch ldy elements (ldy >= N), y_dtype ARCQ_DTYPE_F16 / _F32,
- *      4-byte aligned.
+ *      4-byte aligned (16-byte aligned with ldy % 8 == 0 lets the tiled kernels store whole lines).
  * workspace  device scratch of at least arcq_gemm_workspace_size bytes, 256-byte
  *      aligned (may be NULL when that size is 0); contents undefined afterwards.
  */
