@@ -144,7 +144,9 @@ void quantize_rows_kernel(
     auto off_of = [&](int j, int i) -> uint32_t {
         if constexpr (PACK) {
             uint32_t c = chp[j][i >> 1];
-            asm volatile("" : "+v"(c));          // keeps the unpacking inside the row loop (hoisted, it is 32 registers again)
+            // keeps the unpacking inside the row loop (hoisted, it is 32 registers again): tied to the row number,
+            // and not volatile, which would order the gathers of a lane one behind the other
+            asm("" : "+v"(c) : "s"(row));
             return (i & 1) ? (c >> 15) & 0x1FFFEu : (c & 0xFFFFu) << 1;
         } else {
             return off[j][i];
@@ -212,8 +214,8 @@ void quantize_rows_kernel(
                     for (int e = 0; e < 4; ++e) {
                         const float lo = __half2float(__ushort_as_half((unsigned short)(q4[e] & 0xFFFFu)));
                         const float hi = __half2float(__ushort_as_half((unsigned short)(q4[e] >> 16)));
-                        s8 += (double)(lo * lo);
-                        s8 += (double)(hi * hi);
+                        s8 = __builtin_fma((double)lo, (double)lo, s8);      // the square is exact, one rounding per term
+                        s8 = __builtin_fma((double)hi, (double)hi, s8);
                     }
                     part += tid + p * T < n16 ? s8 : 0.0;               // slots past the row hold a duplicate
                 }
@@ -315,7 +317,7 @@ void quantize_rows_kernel(
                     // into one mixed-precision multiply-add, which rounds once (a different fp16 value once in
                     // some 10^7 elements) and adds +0 (so -0 becomes +0).
                     float prod = __half2float(h) * rstd;
-                    asm volatile("" : "+v"(prod));
+                    asm("" : "+v"(prod));
                     const __half t16 = __float2half_rn(prod);
                     const __half g = GAMMA_REGS
                         ? __ushort_as_half((unsigned short)((gam[j][i >> 1] >> (16 * (i & 1))) & 0xFFFFu))
