@@ -8,8 +8,12 @@ Weight Quantization").  The default workload is the LLaMA-3-8B q_proj prefill sh
 (M=2048, K=4096, N=4096, S=256).
 
 The timed region holds exactly --steps steps and nothing else on the stream; the same steps are
-then repeated with an event after every launch, which gives the per-kernel launch durations the
-rooflines use (those events cost a few microseconds per step, so they stay out of the timed region).
+then repeated (at most 200 of them) with an event after every launch, which gives the per-kernel launch
+durations the rooflines use (those events cost a few microseconds per step, so they stay out of the timed
+region).  The defaults (2000 steps after 300 untimed ones, 0.2 s in all) are long on purpose: for the first
+fifty to a hundred steps after the matrix load sets in this GPU's clock management makes the same GEMM up
+to 20 % slower than it runs from then on, and a 50-step region measures mostly that transient.  Every other
+figure comes from a loop sized the same way (`sustained_ms`: some 20 ms untimed, then some 40 ms timed).
 `detail.rmsnorm_quant_ms` (the quantizer with RMSNorm fused in front) and `detail.mxfp4` (the same step
 in the MXFP4 variant of the format, whose GEMM runs on the scaled FP4 matrix instruction) are reported
 beside the headline figures and do not enter `value`.
@@ -17,7 +21,7 @@ beside the headline figures and do not enter `value`.
 Prints ONE JSON line.  `value` = 2*M*N*K' / step time, in TFLOP/s.  `roofline` prices the dominant
 kernel (the GEMM; fp16 MFMA peak because operands are decoded exactly to fp16).  `cpu_baseline`
 is the numpy oracle timed on the host cores on the same workload.  `also` holds the other
-single-GPU workloads (fewer steps): the HBM-streaming claim of the quantizer is made on
+single-GPU workloads (loop lengths from their own step time): the HBM-streaming claim of the quantizer is made on
 c5_llama70b_down, the decode shapes c3a/c3b are weight-streaming bound (their `gemm_rotating_ms` cycles
 over enough weight copies to exceed the last-level cache, so every launch streams its weight from HBM).
 `s_sweep` times quantizer and GEMM against S at the main workload's shape (Section 3.4: cost linear in
@@ -66,6 +70,36 @@ def gemm_bytes(M, N, Kp, out_bytes=2):
     return (M + N) * (Kp // 2 + Kp // 16) + M * N * out_bytes
 
 
+def sustained_ms(torch, fn, n=None, warm=None, target_ms=40.0, warm_ms=20.0):
+    """Average time of fn() in a loop of back-to-back launches bracketed by two events on the current stream.
+    Without n / warm the loop lengths come from a three-call estimate: about warm_ms of untimed calls first,
+    then about target_ms of timed ones.  Short loops measure the clock transient of this GPU instead of the
+    kernel: for some tens of launches after a matrix-heavy load sets in the same GEMM runs up to 20 % slower
+    than it does a few milliseconds later, and idle gaps of a few microseconds let it run faster than it
+    can when launched back to back."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if n is None or warm is None:
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(3):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        est = max(e0.elapsed_time(e1) / 3, 1e-3)
+        n = int(min(max(target_ms / est, 10), 4000)) if n is None else n
+        warm = int(min(max(warm_ms / est, 3), 2000)) if warm is None else warm
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(n):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n
+
+
 def measure(torch, B, case, steps, warmup, vendor_ref=True):
     """Runs warmup + steps of (quantize_act, gemm) on the current stream; per-kernel times come
     from events recorded on that same stream around each launch inside the timed region."""
@@ -84,6 +118,13 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
     quant = B.prepare_quantize_act(X, perm, S, sTx, ac, asc)
     gemm = B.prepare_gemm(ac, asc, sTx, wc, wsc, sTw, Y, ws)
 
+    def step():
+        quant()
+        gemm()
+    if steps is None:                       # loop lengths from the step's own duration: about 60 ms timed
+        est = sustained_ms(torch, step, 3, 2)
+        steps = int(min(max(60.0 / est, 10), 4000))
+        warmup = int(min(max(20.0 / est, 4), 2000))
     for _ in range(warmup):
         quant()
         gemm()
@@ -101,7 +142,8 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
     dev_ms = first.elapsed_time(last) / steps
     # the same steps again with an event after every launch: per-kernel launch durations for the
     # rooflines (the extra events cost a few microseconds per step, so they stay out of the region above)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    nev = min(steps, 200)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(nev)]
     for e in evs:
         e[0].record()
         quant()
@@ -112,25 +154,20 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
     out = {
         "wall_ms": wall_ms,
         "dev_ms": dev_ms,
-        "quant_ms": sum(e[0].elapsed_time(e[1]) for e in evs) / steps,
-        "gemm_ms": sum(e[1].elapsed_time(e[2]) for e in evs) / steps,
+        "steps": steps,
+        "warmup": warmup,
+        "quant_ms": sum(e[0].elapsed_time(e[1]) for e in evs) / nev,
+        "gemm_ms": sum(e[1].elapsed_time(e[2]) for e in evs) / nev,
+        # the same kernels launched back to back in loops of their own (no event between launches)
+        "quant_loop_ms": sustained_ms(torch, quant),
+        "gemm_loop_ms": sustained_ms(torch, gemm),
     }
     # the quantizer with RMSNorm fused in front (Section 3.3), on the same tensor taken as the
     # pre-norm hidden state: its own figure, not part of the step
     from paper_2601_07475_amd import workloads as wk
     gamma = d(wk.rmsnorm_gamma(wl))
     nq = B.prepare_rmsnorm_quantize_act(X, gamma, 1e-5, perm, S, sTx, ac, asc)
-    for _ in range(3):
-        nq()
-    torch.cuda.synchronize()
-    n = max(3, min(steps, 20))
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-    for e0, e1 in pairs:
-        e0.record()
-        nq()
-        e1.record()
-    torch.cuda.synchronize()
-    out["rmsnorm_quant_ms"] = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / n
+    out["rmsnorm_quant_ms"] = sustained_ms(torch, nq)
     # the MXFP4 variant of the same step (block 32, E8M0 scales; the GEMM runs on the scaled FP4 matrix
     # instruction): its own figures, not part of `value`
     if wl.K % 32 == 0 and S % 32 == 0:
@@ -144,23 +181,8 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
         def mx_step():
             mx_quant()
             mx_gemm()
-        for _ in range(3):
-            mx_step()
-        torch.cuda.synchronize()
-        n = max(3, min(steps, 20))
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(n):
-            mx_step()
-        e1.record()
-        torch.cuda.synchronize()
-        out["mx_step_ms"] = e0.elapsed_time(e1) / n
-        e0.record()
-        for _ in range(n):
-            mx_gemm()
-        e1.record()
-        torch.cuda.synchronize()
-        out["mx_gemm_ms"] = e0.elapsed_time(e1) / n
+        out["mx_step_ms"] = sustained_ms(torch, mx_step)
+        out["mx_gemm_ms"] = sustained_ms(torch, mx_gemm)
     if wl.M <= 128:
         # decode shapes: the packed weight (tens of MB) stays in the 256 MB last-level cache between
         # launches above; rotating over enough copies to exceed it gives the figure with the weight
@@ -169,34 +191,19 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
         ncopy = max(2, -(-384 * 2**20 // wbytes))
         copies = [(wc.clone(), wsc.clone()) for _ in range(ncopy)]
         gemms = [B.prepare_gemm(ac, asc, sTx, c, sc, sTw, Y, ws) for c, sc in copies]
-        for g in gemms:
-            g()
-        torch.cuda.synchronize()
-        n = 2 * ncopy
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(n):
-            gemms[i % ncopy]()
-        e1.record()
-        torch.cuda.synchronize()
-        out["gemm_rotating_ms"] = e0.elapsed_time(e1) / n
+        def rotate():                       # one call = one launch on every copy
+            for g in gemms:
+                g()
+        out["gemm_rotating_ms"] = sustained_ms(torch, rotate) / ncopy
         out["gemm_rotating_copies"] = ncopy
         del copies, gemms
     if vendor_ref:
         # context only: the vendor library's bf16 GEMM (hipBLASLt through torch.matmul) on the
         # unquantized operands, K columns (no augmentation); not part of the product path
         Xb, Wb = X.to(torch.bfloat16), W.to(torch.bfloat16)
-        for _ in range(3):
-            Xb @ Wb.t()
-        torch.cuda.synchronize()
-        n = max(3, min(steps, 20))
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(n):
-            Xb @ Wb.t()
-        e1.record()
-        torch.cuda.synchronize()
-        out["vendor_bf16_gemm_ms"] = e0.elapsed_time(e1) / n
+        Wt = Wb.t()
+        Yb = torch.empty((wl.M, wl.N), dtype=torch.bfloat16, device="cuda")
+        out["vendor_bf16_gemm_ms"] = sustained_ms(torch, lambda: torch.matmul(Xb, Wt, out=Yb))
     return out
 
 
@@ -207,7 +214,9 @@ def summarize(wl, S, t):
     gb = gemm_bytes(wl.M, wl.N, Kp)
     s = {
         "M": wl.M, "K": wl.K, "N": wl.N, "S": S,
+        "steps": t["steps"], "warmup": t["warmup"],
         "step_ms": round(t["dev_ms"], 5), "quant_ms": round(t["quant_ms"], 5), "gemm_ms": round(t["gemm_ms"], 5),
+        "quant_loop_ms": round(t["quant_loop_ms"], 5), "gemm_loop_ms": round(t["gemm_loop_ms"], 5),
         "step_tflops": round(fl / t["dev_ms"] / 1e9, 2),
         "gemm_tflops": round(fl / t["gemm_ms"] / 1e9, 2),
         "gemm_frac_of_f16_mfma_peak": round(fl / t["gemm_ms"] / 1e9 / PEAK_MFMA_F16_TFLOPS, 4),
@@ -235,7 +244,7 @@ def summarize(wl, S, t):
     return s
 
 
-def s_sweep(torch, B, case, values, iters=20):
+def s_sweep(torch, B, case, values):
     """GEMM and quantizer time against the number S of augmented channels at the workload's shape
     (Section 3.4: the cost of compensation is the extra S/K of the reduction dimension, so the GEMM
     time should rise linearly in S from the S = 0 point, which is plain NVFP4 W4A4)."""
@@ -256,21 +265,8 @@ def s_sweep(torch, B, case, values, iters=20):
         ws = torch.empty(max(B.arcq_gemm_workspace_size(wl.M, wl.N, Kp), 1), dtype=torch.uint8, device="cuda")
         quant = B.prepare_quantize_act(X, perm, S, sTx, ac, asc)
         gemm = B.prepare_gemm(ac, asc, sTx, wc, wsc, sTw, Y, ws)
-        for _ in range(3):
-            quant()
-            gemm()
-        torch.cuda.synchronize()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        ev[0].record()
-        for _ in range(iters):
-            quant()
-        ev[1].record()
-        for _ in range(iters):
-            gemm()
-        ev[2].record()
-        torch.cuda.synchronize()
-        rows.append({"S": S, "quant_ms": round(ev[0].elapsed_time(ev[1]) / iters, 5),
-                     "gemm_ms": round(ev[1].elapsed_time(ev[2]) / iters, 5)})
+        rows.append({"S": S, "quant_ms": round(sustained_ms(torch, quant, target_ms=10.0, warm_ms=5.0), 5),
+                     "gemm_ms": round(sustained_ms(torch, gemm, target_ms=30.0, warm_ms=15.0), 5)})
     g0 = rows[0]["gemm_ms"] if rows and rows[0]["S"] == 0 else None
     for r in rows:
         r["gemm_vs_S0"] = round(r["gemm_ms"] / g0, 4) if g0 else None
@@ -341,11 +337,11 @@ def cpu_baseline(case):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="c2_llama8b_q")
     ap.add_argument("--also", default="c4_qwen32b_mlp,c5_llama70b_down,c3a_llama8b_up,c3b_llama8b_down",
-                    help="comma-separated extra workloads reported under 'also' (fewer steps); '' for none")
+                    help="comma-separated extra workloads reported under 'also' (loop lengths from their own step time); '' for none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-vendor-ref", action="store_true")
     ap.add_argument("--s-sweep", default="0,128,256,512,1024,2048",
@@ -388,8 +384,7 @@ def main():
     for name in [n for n in args.also.split(",") if n and n != args.workload]:
         w2 = wk.WORKLOADS[name]
         c2 = wk.make_case(w2)
-        n_steps = 10 if w2.M * w2.N * w2.K > 1e12 else 20
-        also[name] = summarize(w2, c2["S"], measure(torch, B, c2, n_steps, 4, not args.no_vendor_ref))
+        also[name] = summarize(w2, c2["S"], measure(torch, B, c2, None, None, not args.no_vendor_ref))
         del c2
         torch.cuda.empty_cache()
 
