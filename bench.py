@@ -26,7 +26,7 @@ c5_llama70b_down, the decode shapes c3a/c3b are weight-streaming bound (their `g
 over enough weight copies to exceed the last-level cache, so every launch streams its weight from HBM).
 `s_sweep` times quantizer and GEMM against S at the main workload's shape (Section 3.4: cost linear in
 S/K); `machine` holds what the box itself reaches: the plain copy rate and the register-only fp16 matrix
-instruction rate (arcq_probe_mfma_f16).
+instruction rates (arcq_probe_mfma_f16, arcq_probe_mfma_fp4).
 """
 import argparse
 import json
@@ -274,18 +274,17 @@ def s_sweep(torch, B, case, values):
     return rows
 
 
-def mfma_rate(torch, B, iters=4000, reps=3):
-    """fp16 32x32x16 matrix instructions on register operands, four waves per SIMD, no memory traffic:
-    the matrix rate this machine sustains (TFLOP/s), the practical ceiling of the GEMM's roofline."""
+def mfma_rate(torch, probe, B, iters=2000):
+    """Matrix instructions on register operands, four waves per SIMD, no memory traffic: the matrix rate
+    this box sustains (TFLOP/s), the practical ceiling of the GEMM's roofline.  `probe`: B.arcq_probe_mfma_f16
+    (fp16 32x32x16) or B.arcq_probe_mfma_fp4 (scaled FP4 32x32x64)."""
     sink = torch.empty(B.PROBE_SINK_FLOATS, dtype=torch.float32, device="cuda")
-    B.arcq_probe_mfma_f16(200, sink)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    flop = sum(B.arcq_probe_mfma_f16(iters, sink) for _ in range(reps))
-    e1.record()
-    torch.cuda.synchronize()
-    return round(flop / e0.elapsed_time(e1) / 1e9, 1)
+    flop = [0.0]
+
+    def launch():
+        flop[0] = probe(iters, sink)
+    ms = sustained_ms(torch, launch)
+    return round(flop[0] / ms / 1e9, 1)
 
 
 def copy_rate(torch, nbytes=1 << 30, iters=5):
@@ -388,7 +387,8 @@ def main():
         del c2
         torch.cuda.empty_cache()
 
-    mfma_tflops = mfma_rate(torch, B)
+    mfma_tflops = mfma_rate(torch, B.arcq_probe_mfma_f16, B)
+    mfma_fp4_tflops = mfma_rate(torch, B.arcq_probe_mfma_fp4, B)
     sweep = s_sweep(torch, B, case, [int(v) for v in args.s_sweep.split(",") if v]) if args.s_sweep else None
     stream_gbs = copy_rate(torch)
 
@@ -411,9 +411,9 @@ def main():
                                "traffic": traffic.get("arcq_quantize_act"),
                                "note": "this workload (22 MB) is cache-resident: effective GB/s; the HBM-streaming figure is also.c5_llama70b_down.quant_gbs"},
         "detail": s, "also": also, "s_sweep": sweep,
-        "machine": {"device_copy_gbs": stream_gbs, "mfma_f16_tflops": mfma_tflops,
-                    "note": "measured on this box: 1 GiB device-to-device copy (read + write bytes); fp16 32x32x16 "
-                            "matrix instructions on register operands, four waves per SIMD"},
+        "machine": {"device_copy_gbs": stream_gbs, "mfma_f16_tflops": mfma_tflops, "mfma_fp4_tflops": mfma_fp4_tflops,
+                    "note": "measured on this box: 1 GiB device-to-device copy (read + write bytes); fp16 32x32x16 and "
+                            "scaled FP4 32x32x64 matrix instructions on register operands, four waves per SIMD"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case)

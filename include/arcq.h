@@ -184,6 +184,9 @@ arcq_status arcq_check_perm(const int32_t* perm, int64_t K, uint8_t* flags,
  */
 #define ARCQ_PROBE_SINK_FLOATS 262144
 arcq_status arcq_probe_mfma_f16(int iters, float* sink, double* flop_host, void* stream);
+/* The same for the instruction arcq_mx_gemm is built on: 4 * iters scaled FP4 32x32x64 matrix instructions
+ * per wave (both operands E2M1, unit block scales); same arguments, same sink size. */
+arcq_status arcq_probe_mfma_fp4(int iters, float* sink, double* flop_host, void* stream);
 
 /*
  * Offline calibration (Section 3.2 "Adaptive Outlier Identification"), two calls.

@@ -41,6 +41,7 @@ SIGNATURES = {
     "arcq_gemm": (ctypes.c_int, [_vp, _vp, _f32, _vp, _vp, _f32, _i64, _i64, _i64, _vp, ctypes.c_int, _i64,
                                  _vp, _sz, _vp]),
     "arcq_probe_mfma_f16": (ctypes.c_int, [ctypes.c_int, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
+    "arcq_probe_mfma_fp4": (ctypes.c_int, [ctypes.c_int, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
     "arcq_check_perm": (ctypes.c_int, [_vp, _i64, _vp, ctypes.POINTER(ctypes.c_int), _vp]),
 }
 
@@ -333,14 +334,23 @@ def prepare_mx_gemm(a_codes, a_scales, w_codes, w_scales, y):
 PROBE_SINK_FLOATS = 262144
 
 
-def arcq_probe_mfma_f16(iters, sink=None):
-    """Enqueues the matrix-rate probe; returns the floating-point operations of the launch."""
+def _probe(name, iters, sink):
     if sink is None:
         sink = torch.empty(PROBE_SINK_FLOATS, dtype=torch.float32, device="cuda")
     assert sink.is_cuda and sink.dtype == torch.float32 and sink.numel() >= PROBE_SINK_FLOATS and sink.is_contiguous()
     flop = ctypes.c_double(0.0)
-    _check(lib().arcq_probe_mfma_f16(int(iters), _ptr(sink), ctypes.byref(flop), _stream()))
+    _check(getattr(lib(), name)(int(iters), _ptr(sink), ctypes.byref(flop), _stream()))
     return flop.value
+
+
+def arcq_probe_mfma_f16(iters, sink=None):
+    """Enqueues the fp16 matrix-rate probe; returns the floating-point operations of the launch."""
+    return _probe("arcq_probe_mfma_f16", iters, sink)
+
+
+def arcq_probe_mfma_fp4(iters, sink=None):
+    """Enqueues the scaled-FP4 matrix-rate probe; returns the floating-point operations of the launch."""
+    return _probe("arcq_probe_mfma_fp4", iters, sink)
 
 
 def arcq_check_perm(perm):

@@ -212,6 +212,14 @@ arcq_status arcq_probe_mfma_f16(int iters, float* sink, double* flop_host, void*
     return launch_probe_mfma_f16(iters, sink, flop_host, static_cast<hipStream_t>(stream));
 }
 
+arcq_status arcq_probe_mfma_fp4(int iters, float* sink, double* flop_host, void* stream) {
+    clear_error();
+    if (iters < 1 || iters > (1 << 20)) return fail(ARCQ_INVALID_ARG, "arcq_probe_mfma_fp4: iters = %d out of range", iters);
+    if (!sink || !flop_host) return fail(ARCQ_INVALID_ARG, "arcq_probe_mfma_fp4: null pointer");
+    if (!aligned(sink, 4)) return fail(ARCQ_BAD_ALIGN, "arcq_probe_mfma_fp4: sink must be 4-byte aligned");
+    return launch_probe_mfma_fp4(iters, sink, flop_host, static_cast<hipStream_t>(stream));
+}
+
 arcq_status arcq_calib_absmax(const void* x, int64_t M, int64_t K, int64_t ldx, float* colmax, void* stream) {
     clear_error();
     if (arcq_status st = check_KS(K, 0)) return st;

@@ -30,6 +30,7 @@ arcq_status launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
                         void* workspace, size_t workspace_bytes, hipStream_t stream);
 
 arcq_status launch_probe_mfma_f16(int iters, float* sink, double* flop_host, hipStream_t stream);
+arcq_status launch_probe_mfma_fp4(int iters, float* sink, double* flop_host, hipStream_t stream);
 arcq_status launch_check_perm(const int32_t* perm, int64_t K, uint8_t* flags,
                               int* result_host, hipStream_t stream);
 

@@ -603,11 +603,12 @@ def test_mx_full_size_llama8b_qproj():
     assert norm_err(Y[rows], Yref) <= GEMM_TOL_F16
 
 
-def test_matrix_rate_probe_runs_and_counts_its_work():
-    say("arcq_probe_mfma_f16")
+@pytest.mark.parametrize("name,k", [("arcq_probe_mfma_f16", 16), ("arcq_probe_mfma_fp4", 64)])
+def test_matrix_rate_probe_runs_and_counts_its_work(name, k):
+    say(name)
     sink = torch.full((B.PROBE_SINK_FLOATS,), float("nan"), dtype=torch.float32, device="cuda")
-    flop = B.arcq_probe_mfma_f16(3, sink)
+    flop = getattr(B, name)(3, sink)
     torch.cuda.synchronize()
-    assert flop == 4096 * 3 * 4 * 2 * 32 * 32 * 16
+    assert flop == 4096 * 3 * 4 * 2 * 32 * 32 * k
     out = sink.cpu().numpy()
     assert np.all(np.isfinite(out)) and np.any(out != 0)

@@ -186,11 +186,12 @@ def test_variant_entry_points_argument_errors():
     assert (B.LAYOUT_INTERLEAVED, B.SCALE_ROUND_UP) == (1, 2)
 
 
-def test_probe_argument_errors():
-    L = B.lib()
+@pytest.mark.parametrize("name", ["arcq_probe_mfma_f16", "arcq_probe_mfma_fp4"])
+def test_probe_argument_errors(name):
+    probe = getattr(B.lib(), name)
     fl = ctypes.c_double(0)
-    assert L.arcq_probe_mfma_f16(0, FAKE, ctypes.byref(fl), None) == B.INVALID_ARG
-    assert L.arcq_probe_mfma_f16(1 << 21, FAKE, ctypes.byref(fl), None) == B.INVALID_ARG
-    assert L.arcq_probe_mfma_f16(10, None, ctypes.byref(fl), None) == B.INVALID_ARG
-    assert L.arcq_probe_mfma_f16(10, FAKE, None, None) == B.INVALID_ARG
-    assert L.arcq_probe_mfma_f16(10, ctypes.c_void_p(0x10002), ctypes.byref(fl), None) == B.BAD_ALIGN
+    assert probe(0, FAKE, ctypes.byref(fl), None) == B.INVALID_ARG
+    assert probe(1 << 21, FAKE, ctypes.byref(fl), None) == B.INVALID_ARG
+    assert probe(10, None, ctypes.byref(fl), None) == B.INVALID_ARG
+    assert probe(10, FAKE, None, None) == B.INVALID_ARG
+    assert probe(10, ctypes.c_void_p(0x10002), ctypes.byref(fl), None) == B.BAD_ALIGN
