@@ -908,15 +908,27 @@ arcq_status launch_skinny(const uint8_t* a_codes, const uint8_t* a_scales, const
     return check_launch("gemm_skinny_kernel");
 }
 
+// Shapes the weight-streaming kernel serves (alignment permitting): up to 64 rows always; up to 128 rows
+// unless the problem is big enough for the tiled kernels with split K to be faster (measured over
+// N = 1024 .. 28672, K' = 1088 .. 14592 at M = 80, 96, 128: the eight-row-tile variant of the streaming kernel
+// takes about 1 us per 10^6 weights, the tiled path 20-30 us for everything up to 6 * 10^7 weights, more with
+// a short K' that cannot be split).
+static bool skinny_shape(int64_t M, int64_t N, int64_t Kp) {
+    if (M <= 64) return true;
+    if (M > 128) return false;
+    const int64_t weights = N * Kp;
+    return !((Kp >= 4096 && weights >= 20000000) || (Kp >= 8192 && weights >= 12000000));
+}
+
 // Number of runs the reduction dimension is cut into (1: no split).  A function of the shape alone,
-// so that the workspace a caller sizes beforehand matches what the launch uses.  Problems of more
-// than 128 rows with too few 128 x 128 tiles to occupy the chip split K' into runs of at least four
+// so that the workspace a caller sizes beforehand matches what the launch uses.  Problems off the
+// weight-streaming path with too few 128 x 128 tiles to occupy the chip split K' into runs of at least four
 // stages (256 k).  The number of runs minimises a cost in units of one stage time of a tile (about
 // 1.3 us): rounds of workgroups over the 256 CUs times the stages of a run, plus, when split, the
 // write and read of the fp32 partial results at about 3 TB/s.
 int split_k(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nbk = Kp >> 4;
-    if (M <= 128 || (nbk & 3) != 0 || nbk < 8) return 1;
+    if (skinny_shape(M, N, Kp) || (nbk & 3) != 0 || nbk < 8) return 1;
     if (((M + 255) / 256) * ((N + 255) / 256) >= 256 || ((M + 127) / 128) * ((N + 255) / 256) >= 192) return 1;
     const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
     if (tiles > 128) return 1;
@@ -941,7 +953,7 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
                          const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, float alpha, OutT* y,
                          int64_t ldy, float* workspace, hipStream_t stream) {
     const int nbk = (int)(Kp >> 4);
-    if (M <= 128 && (nbk & 1) == 0 &&
+    if (skinny_shape(M, N, Kp) && (nbk & 1) == 0 &&
         ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
         ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 1) == 0) {
         // Weight-streaming path.  Enough waves to keep the weight stream in flight, as few as that allows

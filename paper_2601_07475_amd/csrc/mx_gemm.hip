@@ -286,7 +286,7 @@ __global__ __launch_bounds__(256) void mx_gemm_direct_kernel(
     store_tile_swapped<2, 2>(acc, m0, n0, r, h, M, N, 1.0f, y, ldy, false);
 }
 
-// Weight-streaming kernel for M <= 128 (decode, batched decode, short prefill) and K' % 128 == 0: bound by
+// Weight-streaming kernel for M <= 64 (decode, batched decode) and K' % 128 == 0: bound by
 // reading the packed weights once (17/32 byte per weight).  v_mfma_scale_f32_16x16x128_f8f6f4: lane
 // (i = lane % 16, q = lane / 16) supplies the 32 values of block 4c + q of row i for the 128-k chunk c,
 // with that block's scale byte.  A lane loads 16 bytes of codes per row and chunk (a wave: 16 rows x 64
@@ -470,7 +470,12 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
     const bool offsets_fit = (uint64_t)M * (uint64_t)nb * 16 < 0xFFFF0000ull && (uint64_t)N * (uint64_t)nb * 16 < 0xFFFF0000ull;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
                            ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 3) == 0;
-    if (M <= 128 && (nb & 3) == 0 && aligned16) {
+    // The weight-streaming kernel up to 64 rows, unless the tiled kernels are faster already: from 33 rows on
+    // with many weight rows, for any M with more than 2 * 10^8 weights (measured over N = 1024 .. 28672,
+    // K' = 2176 .. 14592, M = 16 .. 128: on the FP4 instruction a 128- or 256-row tile costs no more than a
+    // 16-row one, so the tiled kernels win as soon as their tiles fill the chip; above 64 rows they always did).
+    const bool streaming = M <= 32 ? N * Kp < 200000000 : M <= 64 && N < 8192;
+    if (streaming && (nb & 3) == 0 && aligned16) {
         const int64_t tiles = (N + 15) / 16;
 #define ARCQ_MX_SKINNY(MT_, NT_, W_, U_) \
     return launch_mx_skinny<MT_, NT_, W_, U_>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream)
@@ -483,12 +488,8 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
             if (tiles >= 800) ARCQ_MX_SKINNY(2, 2, 8, 1);
             ARCQ_MX_SKINNY(2, 1, 8, 2);
         }
-        if (M <= 64) {
-            if (tiles >= 800) ARCQ_MX_SKINNY(4, 2, 8, 1);
-            ARCQ_MX_SKINNY(4, 1, 8, 1);
-        }
-        if (tiles >= 800) ARCQ_MX_SKINNY(8, 2, 4, 1);
-        ARCQ_MX_SKINNY(8, 1, 8, 1);
+        if (tiles >= 800) ARCQ_MX_SKINNY(4, 2, 8, 1);
+        ARCQ_MX_SKINNY(4, 1, 8, 1);
 #undef ARCQ_MX_SKINNY
     }
     if ((nb & 3) == 0 && offsets_fit && aligned16) {

@@ -274,6 +274,9 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     # the same 128 x 256 tiles with K' a multiple of 128: the fp16 output takes the kernel whose wave pairs split
     # every stage (ragged edges, the shortest and a longer reduction), the fp32 output the plain tiled kernel
     (1990, 4070, 192, 64), (2048, 3000, 1024, 128),
+    # 65 to 128 rows with enough weights for the tiled kernels with split K instead of the weight-streaming kernel
+    # (K' >= 4096 with 2 * 10^7 weights, K' >= 8192 with 1.2 * 10^7)
+    (100, 4800, 4096, 256), (128, 1500, 8192, 512),
 ]
 
 
@@ -527,9 +530,12 @@ def test_mx_quantize_every_fp16_value():
 MX_GEMM_SHAPES = [  # M, N, K, S: fallback kernel (K' % 128 != 0), every staged tile configuration, ragged edges
     (1, 1, 32, 0), (77, 200, 64, 32), (130, 129, 96, 32), (16, 512, 512, 0), (128, 256, 256, 0), (257, 131, 1024, 0),
     (300, 77, 2048, 2048), (500, 260, 4096, 128), (16, 1000, 4096, 256), (1990, 4070, 256, 128), (4000, 4100, 96, 32),
-    # weight-streaming kernel: 1, 2, 4, 8 tiles of 16 rows, ragged N, one chunk, many chunks split over the waves
+    # weight-streaming kernel (up to 64 rows): 1, 2, 4 tiles of 16 rows, ragged N, one chunk, many chunks split over the waves
     (8, 40, 128, 0), (20, 300, 512, 128), (33, 77, 2048, 2048), (64, 4097, 256, 128), (100, 260, 4096, 128),
     (17, 14336, 512, 512), (48, 2048, 4096, 1024), (1, 4096, 14336, 256),
+    # where the tiled kernels take over from the weight-streaming one: 33 to 64 rows with at least 8192 weight rows
+    # (and just below), more than 64 rows
+    (48, 8200, 480, 32), (48, 8100, 480, 32), (65, 300, 992, 32),
 ]
 
 
