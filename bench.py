@@ -20,7 +20,9 @@ beside the headline figures and do not enter `value`.
 
 Prints ONE JSON line.  `value` = 2*M*N*K' / step time, in TFLOP/s.  `roofline` prices the dominant
 kernel (the GEMM; fp16 MFMA peak because operands are decoded exactly to fp16).  `cpu_baseline`
-is the numpy oracle timed on the host cores on the same workload.  `also` holds the other
+is the numpy oracle timed on the host cores on the same workload.  `detail.vendor_bf16_gemm_ms` and
+`detail.hand_bf16_gemm_ms` time the unquantized bf16 linear layer over K (the vendor library through torch.matmul, and
+this library's own bf16 kernel arcq_ref_gemm_bf16): the 16-bit baselines of `linear_vs_*` (> 1: the quantized step is faster).  `also` holds the other
 single-GPU workloads (loop lengths from their own step time): the HBM-streaming claim of the quantizer is made on
 c5_llama70b_down, the decode shapes c3a/c3b are weight-streaming bound (their `gemm_rotating_ms` cycles
 over enough weight copies to exceed the last-level cache, so every launch streams its weight from HBM).
@@ -204,6 +206,10 @@ def measure(torch, B, case, steps, warmup, vendor_ref=True):
         Wt = Wb.t()
         Yb = torch.empty((wl.M, wl.N), dtype=torch.bfloat16, device="cuda")
         out["vendor_bf16_gemm_ms"] = sustained_ms(torch, lambda: torch.matmul(Xb, Wt, out=Yb))
+        # and this library's own bf16 kernel on the tiled skeleton of the MXFP4 GEMM (arcq_ref_gemm_bf16); prefill
+        # shapes only: it has no weight-streaming variant, so on the decode shapes it would flatter the quantized path
+        if wl.K % 32 == 0 and wl.M > 128:
+            out["hand_bf16_gemm_ms"] = sustained_ms(torch, B.prepare_ref_gemm_bf16(Xb, Wb, Y))
     return out
 
 
@@ -235,6 +241,9 @@ def summarize(wl, S, t):
     if "vendor_bf16_gemm_ms" in t:
         s["vendor_bf16_gemm_ms"] = round(t["vendor_bf16_gemm_ms"], 5)
         s["linear_vs_vendor_bf16"] = round(t["vendor_bf16_gemm_ms"] / t["dev_ms"], 3)   # > 1: quantized linear is faster
+    if "hand_bf16_gemm_ms" in t:
+        s["hand_bf16_gemm_ms"] = round(t["hand_bf16_gemm_ms"], 5)
+        s["linear_vs_hand_bf16"] = round(t["hand_bf16_gemm_ms"] / t["dev_ms"], 3)
     if "gemm_rotating_ms" in t:
         s["gemm_rotating_ms"] = round(t["gemm_rotating_ms"], 5)
         s["gemm_rotating_copies"] = t["gemm_rotating_copies"]

@@ -189,6 +189,16 @@ arcq_status arcq_probe_mfma_f16(int iters, float* sink, double* flop_host, void*
 arcq_status arcq_probe_mfma_fp4(int iters, float* sink, double* flop_host, void* stream);
 
 /*
+ * Comparison kernel for measurements (no part of the method): the unquantized linear layer y = x w^T on bf16
+ * operands, written on the same tiled skeleton as arcq_mx_gemm (operand rows travel global -> LDS in 128-byte
+ * units, v_mfma_f32_32x32x16_bf16, fp32 accumulation), the 16-bit baseline the quantized path is timed against.
+ * x  device, bf16 [M, K] row-major, pitch K, 16-byte aligned     w  device, bf16 [N, K] row-major, 16-byte aligned
+ * y  device, fp16 [M, N], pitch ldy >= N                         K % 32 == 0, operands below 4 GiB each
+ */
+arcq_status arcq_ref_gemm_bf16(const void* x, const void* w, int64_t M, int64_t N, int64_t K, void* y, int64_t ldy,
+                               void* stream);
+
+/*
  * Offline calibration (Section 3.2 "Adaptive Outlier Identification"), two calls.
  *
  * arcq_calib_absmax folds one batch of calibration activations into the running per-channel

@@ -42,6 +42,7 @@ SIGNATURES = {
                                  _vp, _sz, _vp]),
     "arcq_probe_mfma_f16": (ctypes.c_int, [ctypes.c_int, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
     "arcq_probe_mfma_fp4": (ctypes.c_int, [ctypes.c_int, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
+    "arcq_ref_gemm_bf16": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp]),
     "arcq_check_perm": (ctypes.c_int, [_vp, _i64, _vp, ctypes.POINTER(ctypes.c_int), _vp]),
 }
 
@@ -360,3 +361,25 @@ def arcq_check_perm(perm):
     res = ctypes.c_int(-1)
     _check(lib().arcq_check_perm(_ptr(perm), K, _ptr(flags), ctypes.byref(res), _stream()))
     return res.value == 1
+
+
+def prepare_ref_gemm_bf16(x, w, y):
+    """The hand-written bf16 comparison GEMM y = x w^T (x [M, K], w [N, K] bf16, y [M, N] fp16) as a prepared call."""
+    for t in (x, w):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()
+    M, K = x.shape
+    N = w.shape[0]
+    assert w.shape[1] == K and y.shape == (M, N) and y.dtype == torch.float16 and y.stride(1) == 1
+    fn = lib().arcq_ref_gemm_bf16
+    args = (_ptr(x), _ptr(w), M, N, K, _ptr(y), y.stride(0) if M > 1 else N, _stream())
+
+    def call():
+        _check(fn(*args))
+    return call
+
+
+def arcq_ref_gemm_bf16(x, w, y=None):
+    if y is None:
+        y = torch.empty((x.shape[0], w.shape[0]), dtype=torch.float16, device=x.device)
+    prepare_ref_gemm_bf16(x, w, y)()
+    return y

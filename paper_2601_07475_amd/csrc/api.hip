@@ -220,6 +220,20 @@ arcq_status arcq_probe_mfma_fp4(int iters, float* sink, double* flop_host, void*
     return launch_probe_mfma_fp4(iters, sink, flop_host, static_cast<hipStream_t>(stream));
 }
 
+arcq_status arcq_ref_gemm_bf16(const void* x, const void* w, int64_t M, int64_t N, int64_t K, void* y, int64_t ldy,
+                               void* stream) {
+    clear_error();
+    if (M < 0 || N <= 0 || K <= 0 || K > ARCQ_MAX_K || (K & 31) != 0) return fail(ARCQ_BAD_SHAPE, "arcq_ref_gemm_bf16: M = %lld, N = %lld, K = %lld (K %% 32 == 0)", (long long)M, (long long)N, (long long)K);
+    if (ldy < N) return fail(ARCQ_BAD_SHAPE, "arcq_ref_gemm_bf16: ldy = %lld < N", (long long)ldy);
+    if ((uint64_t)M * (uint64_t)K * 2 >= 0xFFFF0000ull || (uint64_t)N * (uint64_t)K * 2 >= 0xFFFF0000ull)
+        return fail(ARCQ_BAD_SHAPE, "arcq_ref_gemm_bf16: an operand of 4 GiB or more");
+    if (M == 0) return ARCQ_OK;
+    if (!x || !w || !y) return fail(ARCQ_INVALID_ARG, "arcq_ref_gemm_bf16: null pointer");
+    if (!aligned(x, 16) || !aligned(w, 16)) return fail(ARCQ_BAD_ALIGN, "arcq_ref_gemm_bf16: operands must be 16-byte aligned");
+    if (!aligned(y, 2)) return fail(ARCQ_BAD_ALIGN, "arcq_ref_gemm_bf16: y must be 2-byte aligned");
+    return launch_ref_gemm_bf16(x, w, M, N, K, static_cast<_Float16*>(y), ldy, static_cast<hipStream_t>(stream));
+}
+
 arcq_status arcq_calib_absmax(const void* x, int64_t M, int64_t K, int64_t ldx, float* colmax, void* stream) {
     clear_error();
     if (arcq_status st = check_KS(K, 0)) return st;

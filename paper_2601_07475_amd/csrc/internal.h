@@ -31,6 +31,8 @@ arcq_status launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
 
 arcq_status launch_probe_mfma_f16(int iters, float* sink, double* flop_host, hipStream_t stream);
 arcq_status launch_probe_mfma_fp4(int iters, float* sink, double* flop_host, hipStream_t stream);
+arcq_status launch_ref_gemm_bf16(const void* x, const void* w, int64_t M, int64_t N, int64_t K, _Float16* y, int64_t ldy,
+                                 hipStream_t stream);
 arcq_status launch_check_perm(const int32_t* perm, int64_t K, uint8_t* flags,
                               int* result_host, hipStream_t stream);
 

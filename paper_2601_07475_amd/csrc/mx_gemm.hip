@@ -41,12 +41,14 @@ __device__ __forceinline__ float16v mfma_mx(const uint4& a, const uint4& b, cons
 // choosing which global piece a lane fetches (a wave-wide copy writes lane l to base + 16 l).
 // When K' is an odd multiple of 128 the last unit is half a unit: its copies re-fetch the first half
 // for the missing second half (never used, in bounds).
-template <int WM, int WN, int GM, int GN>
+// BF16: the same skeleton for plain bf16 operands (the comparison kernel arcq_ref_gemm_bf16): a row of a unit is 128
+// bytes = 64 bf16 values, there are no scale bytes, and a k-step is one v_mfma_f32_32x32x16_bf16.
+template <int WM, int WN, int GM, int GN, bool BF16 = false>
 struct MxCfg {
     static constexpr int BM = 32 * WM * GM, BN = 32 * WN * GN;
     static constexpr int NT = 64 * GM * GN;
     static constexpr int NA = (BM * 8 + NT - 1) / NT, NW = (BN * 8 + NT - 1) / NT;       // 16-byte pieces of codes
-    static constexpr int NAS = (BM * 2 + NT - 1) / NT, NWS = (BN * 2 + NT - 1) / NT;     // 4-byte words of scales
+    static constexpr int NAS = BF16 ? 0 : (BM * 2 + NT - 1) / NT, NWS = BF16 ? 0 : (BN * 2 + NT - 1) / NT;     // 4-byte words of scales
     static constexpr int NDMA = NA + NW + NAS + NWS;
     static constexpr int A_CODES = 0;
     static constexpr int W_CODES = NA * NT * 16;
@@ -58,12 +60,14 @@ struct MxCfg {
     static_assert(NDMA * (NUNIT - 1) < 64, "the counted wait needs the copies of NUNIT - 1 units to fit the counter");
 };
 
-template <int WM, int WN, int GM, int GN, typename OutT>
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <int WM, int WN, int GM, int GN, typename OutT, bool BF16 = false>
 __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N, int nb,
     OutT* __restrict__ y, int64_t ldy, int tiles_m, int tiles_n) {
-    using C = MxCfg<WM, WN, GM, GN>;
+    using C = MxCfg<WM, WN, GM, GN, BF16>;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     // workgroup -> tile: a contiguous run of the tile sequence per XCD, column-major groups of 8 tile rows
@@ -146,6 +150,7 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
         for (int j = 0; j < WN; ++j) fw[slot][j] = *reinterpret_cast<const uint4*>(st + rd_w + j * 4096 + pc[t]);
     };
     auto read_scales = [&](const uint8_t* st, uint2 (&da)[WM], uint2 (&dw)[WN]) {
+        if (BF16) return;
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
             const uint2 v = *reinterpret_cast<const uint2*>(st + rd_as + i * 256);
@@ -192,8 +197,12 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     // weights as the row operand: see store_tile_swapped
-                    acc[i][j] = mfma_mx(fw[t & 1][j], fa[t & 1][i], acc[i][j], (int)(t < 2 ? sw[j].x : sw[j].y),
-                                        (int)(t < 2 ? sa[i].x : sa[i].y), t & 1);
+                    if constexpr (BF16)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw[t & 1][j]),
+                                                                            __builtin_bit_cast(bf16x8, fa[t & 1][i]), acc[i][j], 0, 0, 0);
+                    else
+                        acc[i][j] = mfma_mx(fw[t & 1][j], fa[t & 1][i], acc[i][j], (int)(t < 2 ? sw[j].x : sw[j].y),
+                                            (int)(t < 2 ? sa[i].x : sa[i].y), t & 1);
                     __builtin_amdgcn_sched_barrier(0);
                     if (NSTEPS == 4 && q < C::NDMA) {
                         issue_one(q, fetch, bufd);
@@ -201,10 +210,12 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
                     }
                 }
         }
+        if constexpr (!BF16) {
 #pragma unroll
-        for (int i = 0; i < WM; ++i) sa[i] = sa_n[i];
+            for (int i = 0; i < WM; ++i) sa[i] = sa_n[i];
 #pragma unroll
-        for (int j = 0; j < WN; ++j) sw[j] = sw_n[j];
+            for (int j = 0; j < WN; ++j) sw[j] = sw_n[j];
+        }
         buf = buf1;
     };
     static_assert(C::NDMA <= 3 * NM, "copies are issued during the first three k-steps of a unit");
@@ -448,11 +459,11 @@ arcq_status launch_mx_skinny(const uint8_t* a_codes, const uint8_t* a_scales, co
     return check_launch("mx_gemm_skinny_kernel");
 }
 
-template <int WM, int WN, int GM, int GN, typename OutT>
+template <int WM, int WN, int GM, int GN, typename OutT, bool BF16 = false>
 arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                              const uint8_t* w_scales, int M, int N, int nb, OutT* y, int64_t ldy, hipStream_t stream) {
-    using C = MxCfg<WM, WN, GM, GN>;
-    auto kern = mx_gemm_staged_kernel<WM, WN, GM, GN, OutT>;
+    using C = MxCfg<WM, WN, GM, GN, BF16>;
+    auto kern = mx_gemm_staged_kernel<WM, WN, GM, GN, OutT, BF16>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
@@ -508,6 +519,20 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
 }
 
 }  // namespace
+
+// Comparison kernel: y = x w^T for plain bf16 operands (x [M, K], w [N, K], row-major, 16-byte aligned, K % 32 == 0)
+// on the tiled skeleton above, fp32 accumulation, fp16 output.  nb counts 16-byte pieces of a row.
+arcq_status launch_ref_gemm_bf16(const void* x, const void* w, int64_t M, int64_t N, int64_t K, _Float16* y, int64_t ldy,
+                                 hipStream_t stream) {
+    const uint8_t* a = static_cast<const uint8_t*>(x);
+    const uint8_t* b = static_cast<const uint8_t*>(w);
+    const int nb = (int)(K >> 3);
+    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+    if (t256 >= 256) return launch_mx_staged<4, 4, 2, 2, _Float16, true>(a, nullptr, b, nullptr, (int)M, (int)N, nb, y, ldy, stream);
+    const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
+    if (t128x256 >= 192) return launch_mx_staged<2, 4, 2, 2, _Float16, true>(a, nullptr, b, nullptr, (int)M, (int)N, nb, y, ldy, stream);
+    return launch_mx_staged<2, 2, 2, 2, _Float16, true>(a, nullptr, b, nullptr, (int)M, (int)N, nb, y, ldy, stream);
+}
 
 arcq_status launch_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                            const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy,

@@ -618,3 +618,15 @@ def test_matrix_rate_probe_runs_and_counts_its_work(name, k):
     assert flop == 4096 * 3 * 4 * 2 * 32 * 32 * k
     out = sink.cpu().numpy()
     assert np.all(np.isfinite(out)) and np.any(out != 0)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 8, 32), (77, 200, 96), (300, 260, 4096), (2048, 3072, 352), (4000, 4100, 128)])
+def test_ref_gemm_bf16_against_fp64(M, N, K):
+    """The bf16 comparison kernel (every tile configuration, ragged edges, a half unit at the end of K)."""
+    say(f"ref_gemm_bf16 M={M} N={N} K={K}")
+    g = torch.Generator().manual_seed(41 + M)
+    x = torch.randn((M, K), generator=g).to(torch.bfloat16)
+    w = (0.05 * torch.randn((N, K), generator=g)).to(torch.bfloat16)
+    Y = B.arcq_ref_gemm_bf16(x.cuda(), w.cuda()).float().cpu().numpy()
+    Yref = x.double().numpy() @ w.double().numpy().T
+    assert norm_err(Y, Yref) <= GEMM_TOL_F16

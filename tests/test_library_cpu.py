@@ -195,3 +195,12 @@ def test_probe_argument_errors(name):
     assert probe(10, None, ctypes.byref(fl), None) == B.INVALID_ARG
     assert probe(10, FAKE, None, None) == B.INVALID_ARG
     assert probe(10, ctypes.c_void_p(0x10002), ctypes.byref(fl), None) == B.BAD_ALIGN
+
+
+def test_ref_gemm_bf16_argument_errors():
+    L = B.lib()
+    assert L.arcq_ref_gemm_bf16(FAKE, FAKE, 8, 8, 48, FAKE, 8, None) == B.BAD_SHAPE          # K % 32
+    assert L.arcq_ref_gemm_bf16(FAKE, FAKE, 8, 8, 64, FAKE, 4, None) == B.BAD_SHAPE          # ldy < N
+    assert L.arcq_ref_gemm_bf16(None, FAKE, 8, 8, 64, FAKE, 8, None) == B.INVALID_ARG
+    assert L.arcq_ref_gemm_bf16(ctypes.c_void_p(0x10008), FAKE, 8, 8, 64, FAKE, 8, None) == B.BAD_ALIGN
+    assert L.arcq_ref_gemm_bf16(FAKE, FAKE, 0, 8, 64, FAKE, 8, None) == B.OK                # empty
