@@ -194,6 +194,17 @@ void quantize_rows_kernel(
         }
 
         float rstd = 1.0f;
+        // KEEP: the lane's gathered values stay in registers (as fp32) from the statistics to the main pass, so the
+        // statistics need no second read and conversion of the row (not with the packed channel indices: no room)
+        constexpr bool KEEP = NORM == 1 && BPT <= 2;
+        float xf[KEEP ? BPT : 1][16];
+        if (KEEP) {
+#pragma unroll
+            for (int j = 0; j < BPT; ++j)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    xf[j][i] = __half2float(*reinterpret_cast<const __half*>(lds_row + base + off_of(j, i)));
+        }
         if (NORM) {
             // Mean of squares, defined with an EXACT sum (no summation order enters the result).
             // Fast path: a plain fp64 sum S^ of the squares (each exact in fp32).  Every term passes through
@@ -203,7 +214,20 @@ void quantize_rows_kernel(
             // rounding is monotone.  If the two agree, that is the answer.
             // Otherwise (a row whose mean sits within delta of an fp32 rounding boundary, a few in 10^5)
             // the workgroup redoes the sum in integer arithmetic below.
-            if (!force_exact) {
+            if (!force_exact && KEEP) {
+                // every channel of the row is gathered by exactly one lane (perm is a permutation)
+                double part = 0.0;
+#pragma unroll
+                for (int j = 0; j < BPT; ++j) {
+                    double s16 = 0.0;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) s16 = __builtin_fma((double)xf[j][i], (double)xf[j][i], s16);
+                    part += tid + j * T < nb ? s16 : 0.0;               // lanes past the last block hold a duplicate
+                }
+                part = row16_sum(part);
+                if ((tid & 15) == 0) lds_add_f64(acc, part);
+                wait_lgkmcnt0();
+            } else if (!force_exact) {
                 // each lane sums the contiguous 16-byte pieces it copied itself: wide, conflict-free reads
                 double part = 0.0;
 #pragma unroll
@@ -250,8 +274,8 @@ void quantize_rows_kernel(
                     double p_aa = 0.0, p_ab = 0.0, p_bb = 0.0;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const __half h = *reinterpret_cast<const __half*>(lds_row + base + off_of(j, i));
-                        const float s16 = fabsf(__half2float(h)) * 16.0f;   // exact, < 2^20, a multiple of 2^-20
+                        const float xv = KEEP ? xf[j][i] : __half2float(*reinterpret_cast<const __half*>(lds_row + base + off_of(j, i)));
+                        const float s16 = fabsf(xv) * 16.0f;                // exact, < 2^20, a multiple of 2^-20
                         const float fa = truncf(s16);
                         const float fb = (s16 - fa) * 0x1p20f;              // exact
                         const double da = (double)fa, db = (double)fb;
@@ -310,13 +334,12 @@ void quantize_rows_kernel(
             float v[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const __half h = *reinterpret_cast<const __half*>(lds_row + base + off_of(j, i));
                 if (NORM) {
                     // t = fl16(fl32(x * rstd)): two roundings, as the reference layer does it.  The product is
                     // pinned to a register between them; left alone the compiler fuses multiply and conversion
                     // into one mixed-precision multiply-add, which rounds once (a different fp16 value once in
                     // some 10^7 elements) and adds +0 (so -0 becomes +0).
-                    float prod = __half2float(h) * rstd;
+                    float prod = (KEEP ? xf[j][i] : __half2float(*reinterpret_cast<const __half*>(lds_row + base + off_of(j, i)))) * rstd;
                     asm("" : "+v"(prod));
                     const __half t16 = __float2half_rn(prod);
                     const __half g = GAMMA_REGS
@@ -325,7 +348,7 @@ void quantize_rows_kernel(
                     // fp16 times fp16 rounded once to fp16
                     v[i] = __half2float(__hmul(t16, g));
                 } else {
-                    v[i] = __half2float(h);
+                    v[i] = __half2float(*reinterpret_cast<const __half*>(lds_row + base + off_of(j, i)));
                 }
             }
             uint32_t sbyte, lo, hi;
