@@ -442,7 +442,7 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// 128 x 256 tiles for problems with about one such tile per CU (2048 x 4096 has 256 of them), fp16 output.
+// 128 x 256 tiles for problems with about one such tile per CU (2048 x 4096 has 256 of them).
 // Same tile, stage ring and copies as gemm_staged_kernel<2, 2, 2, 4>, but the eight waves form a
 // 2 (rows) x 2 (columns) x 2 (k) grid: a wave computes a 64 x 128 sub-tile (2 x 4 fragments: six fragment
 // decodes per eight MFMAs instead of four per four, the decode being what keeps this tile shape from the
@@ -645,12 +645,20 @@ __global__ __launch_bounds__(512) void gemm_kpair_kernel(
     wait_lgkmcnt0();
     wg_barrier();                               // every wave has read its partner's last round
     const int m0 = wg_m0 + wrow0, n0 = wg_n0 + wcol0;
-    const bool vec_ok = (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
-    uint8_t* region = lds + wave * (epilogue_lds_bytes(WN) / 2);
-    if (mine == 0)
-        store_fragment_rows_f16_via_lds<WM, WN, 0, 1>(acc, region, m0, n0, lane, M, N, alpha, y, ldy, vec_ok);
-    else
-        store_fragment_rows_f16_via_lds<WM, WN, 1, 1>(acc, region, m0, n0, lane, M, N, alpha, y, ldy, vec_ok);
+    if constexpr (std::is_same<OutT, _Float16>::value) {
+        const bool vec_ok = (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
+        uint8_t* region = lds + wave * (epilogue_lds_bytes(WN) / 2);
+        if (mine == 0)
+            store_fragment_rows_f16_via_lds<WM, WN, 0, 1>(acc, region, m0, n0, lane, M, N, alpha, y, ldy, vec_ok);
+        else
+            store_fragment_rows_f16_via_lds<WM, WN, 1, 1>(acc, region, m0, n0, lane, M, N, alpha, y, ldy, vec_ok);
+    } else {
+        const bool vec_ok = (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
+        if (mine == 0)
+            store_fragment_row_swapped<WM, WN, 0>(acc, m0, n0, r, h, M, N, alpha, y, ldy, vec_ok);
+        else
+            store_fragment_row_swapped<WM, WN, 1>(acc, m0, n0, r, h, M, N, alpha, y, ldy, vec_ok);
+    }
 }
 
 // y = alpha * (sum of the `splits` fp32 partial results [M, N], added in index order).
@@ -994,13 +1002,12 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
         // 128 x 256 tiles with 8 waves of 64 x 64 (two per SIMD): 5 % faster than 4 waves of 64 x 128 on the
         // 2048 x 4096 x 4352 problem; on the large shapes 4 and 8 waves measure the same
         if (t128x256 >= 192) {
-            // fp16 output and whole stages: the variant whose wave pairs split every stage (6 % faster on the
-            // 2048 x 4096 x 4352 problem with real data, 10 % with random operands; the environment switch
-            // keeps the plain variant reachable for comparisons)
-            if constexpr (std::is_same<OutT, _Float16>::value) {
+            // whole stages: the variant whose wave pairs split every stage (6 % faster on the 2048 x 4096 x 4352
+            // problem; the environment switch keeps the plain variant reachable for comparisons)
+            {
                 if ((nbk & 7) == 0 && nbk >= 16 && !std::getenv("ARCQ_NO_KPAIR")) {
                     using C = StagedCfg<2, 2, 2, 4>;
-                    auto kern = gemm_kpair_kernel<_Float16>;
+                    auto kern = gemm_kpair_kernel<OutT>;
                     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
                     if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));

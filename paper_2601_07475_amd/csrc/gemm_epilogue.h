@@ -21,31 +21,38 @@ __device__ __forceinline__ void store4(_Float16* p, float a, float b, float c, f
     typedef _Float16 half4v __attribute__((ext_vector_type(4)));
     *reinterpret_cast<half4v*>(p) = half4v{(_Float16)a, (_Float16)b, (_Float16)c, (_Float16)d};
 }
+// fragment row I of the tile
+template <int WM, int WN, int I, typename OutT>
+__device__ __forceinline__ void store_fragment_row_swapped(const float16v (&acc)[WM][WN], int m0, int n0, int r, int h, int M,
+                                                           int N, float alpha, OutT* __restrict__ y, int64_t ldy, bool vec_ok) {
+    const int m = m0 + 32 * I + r;
+    if (m >= M) return;
+    OutT* yrow = y + (int64_t)m * ldy;
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int n = n0 + 32 * j + 8 * g + 4 * h;
+            const float v0 = acc[I][j][4 * g] * alpha, v1 = acc[I][j][4 * g + 1] * alpha,
+                        v2 = acc[I][j][4 * g + 2] * alpha, v3 = acc[I][j][4 * g + 3] * alpha;
+            if (vec_ok && n + 3 < N) {
+                store4(yrow + n, v0, v1, v2, v3);
+            } else {
+                if (n < N) store_out(yrow + n, v0);
+                if (n + 1 < N) store_out(yrow + n + 1, v1);
+                if (n + 2 < N) store_out(yrow + n + 2, v2);
+                if (n + 3 < N) store_out(yrow + n + 3, v3);
+            }
+        }
+}
 template <int WM, int WN, typename OutT>
 __device__ __forceinline__ void store_tile_swapped(const float16v (&acc)[WM][WN], int m0, int n0, int r, int h, int M,
                                                    int N, float alpha, OutT* __restrict__ y, int64_t ldy, bool vec_ok) {
-#pragma unroll
-    for (int i = 0; i < WM; ++i) {
-        const int m = m0 + 32 * i + r;
-        if (m >= M) continue;
-        OutT* yrow = y + (int64_t)m * ldy;
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + 32 * j + 8 * g + 4 * h;
-                const float v0 = acc[i][j][4 * g] * alpha, v1 = acc[i][j][4 * g + 1] * alpha,
-                            v2 = acc[i][j][4 * g + 2] * alpha, v3 = acc[i][j][4 * g + 3] * alpha;
-                if (vec_ok && n + 3 < N) {
-                    store4(yrow + n, v0, v1, v2, v3);
-                } else {
-                    if (n < N) store_out(yrow + n, v0);
-                    if (n + 1 < N) store_out(yrow + n + 1, v1);
-                    if (n + 2 < N) store_out(yrow + n + 2, v2);
-                    if (n + 3 < N) store_out(yrow + n + 3, v3);
-                }
-            }
-    }
+    store_fragment_row_swapped<WM, WN, 0>(acc, m0, n0, r, h, M, N, alpha, y, ldy, vec_ok);
+    if constexpr (WM > 1) store_fragment_row_swapped<WM, WN, 1>(acc, m0, n0, r, h, M, N, alpha, y, ldy, vec_ok);
+    if constexpr (WM > 2) store_fragment_row_swapped<WM, WN, 2>(acc, m0, n0, r, h, M, N, alpha, y, ldy, vec_ok);
+    if constexpr (WM > 3) store_fragment_row_swapped<WM, WN, 3>(acc, m0, n0, r, h, M, N, alpha, y, ldy, vec_ok);
+    static_assert(WM <= 4, "up to four fragment rows");
 }
 
 // fp16 output through the LDS, so that the global stores are whole lines: in the accumulator layout a

@@ -271,8 +271,8 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     (256, 512, 4096, 256), (300, 260, 4160, 64), (130, 129, 2048, 64), (200, 140, 576, 64), (384, 1000, 1024, 64),
     # ragged edges in every tile configuration of the staged kernel: 128 x 256 tiles (8 waves), 256 x 256 tiles
     (1990, 4070, 256, 64), (4000, 4100, 128, 64),
-    # the same 128 x 256 tiles with K' a multiple of 128: the fp16 output takes the kernel whose wave pairs split
-    # every stage (ragged edges, the shortest and a longer reduction), the fp32 output the plain tiled kernel
+    # the same 128 x 256 tiles with K' a multiple of 128: the kernel whose wave pairs split every stage
+    # (ragged edges, the shortest and a longer reduction, both output types)
     (1990, 4070, 192, 64), (2048, 3000, 1024, 128),
     # 65 to 128 rows with enough weights for the tiled kernels with split K instead of the weight-streaming kernel
     # (K' >= 4096 with 2 * 10^7 weights, K' >= 8192 with 1.2 * 10^7)
