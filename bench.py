@@ -48,11 +48,11 @@ PEAK_MFMA_FP4_TFLOPS = 10100.0 # MI355X dense fp4 MFMA (the MXFP4 variant's GEMM
 # profiles/), scaled by the factor the same counters read for a plain copy of known size.
 # workload -> kernel -> bytes; None where not measured.
 MEASURED_TRAFFIC = {
-    "c2_llama8b_q": {"arcq_gemm": 57349348, "arcq_quantize_act": 22006789, "arcq_rmsnorm_quantize_act": 22096896, "arcq_mx_quantize_act": 21762193, "arcq_mx_gemm": 54879245},
-    "c4_qwen32b_mlp": {"arcq_gemm": 779782435, "arcq_quantize_act": 55165612, "arcq_rmsnorm_quantize_act": 55242153, "arcq_mx_quantize_act": 54500792, "arcq_mx_gemm": 734658248},
-    "c5_llama70b_down": {"arcq_gemm": 1782298748, "arcq_quantize_act": 621416061, "arcq_rmsnorm_quantize_act": 622472161, "arcq_mx_quantize_act": 613181765, "arcq_mx_gemm": 1694873648},
-    "c3a_llama8b_up": {"arcq_gemm": 36247602, "arcq_quantize_act": 353792, "arcq_rmsnorm_quantize_act": 443904, "arcq_mx_quantize_act": 369152, "arcq_mx_gemm": 34121577},
-    "c3b_llama8b_down": {"arcq_gemm": 35075049, "arcq_quantize_act": 1101312, "arcq_rmsnorm_quantize_act": 1355264, "arcq_mx_quantize_act": 1111552, "arcq_mx_gemm": 32970183},
+    "c2_llama8b_q": {"arcq_gemm": 57334051, "arcq_quantize_act": 22006789, "arcq_rmsnorm_quantize_act": 22096896, "arcq_mx_quantize_act": 21727232, "arcq_mx_gemm": 54879243},
+    "c4_qwen32b_mlp": {"arcq_gemm": 779679605, "arcq_quantize_act": 55196810, "arcq_rmsnorm_quantize_act": 55242245, "arcq_mx_quantize_act": 54475079, "arcq_mx_gemm": 735563373},
+    "c5_llama70b_down": {"arcq_gemm": 1782204367, "arcq_quantize_act": 621205442, "arcq_rmsnorm_quantize_act": 622437157, "arcq_mx_quantize_act": 612800491, "arcq_mx_gemm": 1694875754},
+    "c3a_llama8b_up": {"arcq_gemm": 36219818, "arcq_quantize_act": 353792, "arcq_rmsnorm_quantize_act": 443904, "arcq_mx_quantize_act": 334336, "arcq_mx_gemm": 34167573},
+    "c3b_llama8b_down": {"arcq_gemm": 35089088, "arcq_quantize_act": 1101312, "arcq_rmsnorm_quantize_act": 1355264, "arcq_mx_quantize_act": 1076736, "arcq_mx_gemm": 32989406},
 }
 
 
