@@ -239,7 +239,7 @@ arcq_status arcq_calib_select(const float* colmax, int64_t K, int32_t* perm, int
  * so arcq_mx_gemm needs no decode:
  *   y[m, n] = sum_b 2^(sa[m,b]-127) 2^(sw[n,b]-127) sum_{i<32} qa[m,32b+i] qw[n,32b+i],  fp32 accumulation
  * (Section 3.2 eq. (2)); Kp % 32 == 0; codes 4-byte aligned (16-byte alignment and Kp % 128 == 0 select the
- * fast kernel); y as in arcq_gemm.  No workspace.
+ * fast kernel); y as in arcq_gemm.  No workspace (see arcq_mx_gemm_ws below).
  */
 arcq_status arcq_mx_packed_sizes(int64_t rows, int64_t K, int64_t S,
                                  size_t* codes_bytes, size_t* scales_bytes);
@@ -253,6 +253,20 @@ arcq_status arcq_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
                          const uint8_t* w_codes, const uint8_t* w_scales,
                          int64_t M, int64_t N, int64_t Kp,
                          void* y, int y_dtype, int64_t ldy, void* stream);
+/*
+ * arcq_mx_gemm with a workspace: problems with few output tiles and a long reduction dimension (a few hundred
+ * rows against a down-projection) split K' into runs whose fp32 partial results go through the workspace and are
+ * added in index order by a second kernel (same result up to the order of the fp32 additions).
+ * arcq_mx_gemm_workspace_size: bytes needed for this shape (may be 0; host arithmetic only).
+ * workspace  device scratch of at least that many bytes, 256-byte aligned; may be null when 0 bytes are needed.
+ *            ARCQ_WORKSPACE_TOO_SMALL otherwise.  Calls that share a workspace must not overlap.
+ */
+arcq_status arcq_mx_gemm_workspace_size(int64_t M, int64_t N, int64_t Kp, size_t* bytes);
+arcq_status arcq_mx_gemm_ws(const uint8_t* a_codes, const uint8_t* a_scales,
+                            const uint8_t* w_codes, const uint8_t* w_scales,
+                            int64_t M, int64_t N, int64_t Kp,
+                            void* y, int y_dtype, int64_t ldy,
+                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * The same two variants for MXFP4 (flags as for arcq_quantize_act_ex, blocks of 32):

@@ -35,6 +35,8 @@ SIGNATURES = {
     "arcq_mx_quantize_act": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
     "arcq_mx_pack_weight": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
     "arcq_mx_gemm": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, ctypes.c_int, _i64, _vp]),
+    "arcq_mx_gemm_workspace_size": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
+    "arcq_mx_gemm_ws": (ctypes.c_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, ctypes.c_int, _i64, _vp, _sz, _vp]),
     "arcq_calib_absmax": (ctypes.c_int, [_vp, _i64, _i64, _i64, _vp, _vp]),
     "arcq_calib_select": (ctypes.c_int, [_vp, _i64, _vp, _vp, ctypes.POINTER(ctypes.c_int), _vp]),
     "arcq_gemm_workspace_size": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
@@ -250,8 +252,16 @@ def arcq_mx_pack_weight_ex(w, perm, S, flags, codes=None, scales=None):
     return _mx_quantize(_mx_with_flags(lib().arcq_mx_pack_weight_ex, flags), w, perm, S, codes, scales)
 
 
-def arcq_mx_gemm(a_codes, a_scales, w_codes, w_scales, out_dtype=torch.float16, y=None):
-    """MXFP4: y[M, N] = deq(A) deq(W)^T over K' on the scaled FP4 matrix instruction; returns y."""
+def arcq_mx_gemm_workspace_size(M, N, Kp):
+    b = _sz(0)
+    _check(lib().arcq_mx_gemm_workspace_size(M, N, Kp, ctypes.byref(b)))
+    return b.value
+
+
+def arcq_mx_gemm(a_codes, a_scales, w_codes, w_scales, out_dtype=torch.float16, y=None, workspace=None):
+    """MXFP4: y[M, N] = deq(A) deq(W)^T over K' on the scaled FP4 matrix instruction; returns y.
+    workspace: a uint8 tensor of at least arcq_mx_gemm_workspace_size bytes lets few-tile problems split K'
+    (arcq_mx_gemm_ws); without one the plain entry point runs."""
     for t in (a_codes, a_scales, w_codes, w_scales):
         assert t.is_cuda and t.dtype == torch.uint8 and t.is_contiguous()
     M, N = a_codes.shape[0], w_codes.shape[0]
@@ -262,8 +272,14 @@ def arcq_mx_gemm(a_codes, a_scales, w_codes, w_scales, out_dtype=torch.float16, 
         y = torch.empty((M, N), dtype=out_dtype, device=a_codes.device)
     assert y.shape == (M, N) and y.stride(1) == 1 and y.dtype in (torch.float16, torch.float32)
     ldy = y.stride(0) if M > 1 else max(N, y.stride(0))
-    _check(lib().arcq_mx_gemm(_ptr(a_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), M, N, Kp, _ptr(y),
-                              DTYPE_F16 if y.dtype == torch.float16 else DTYPE_F32, ldy, _stream()))
+    dt = DTYPE_F16 if y.dtype == torch.float16 else DTYPE_F32
+    if workspace is not None:
+        assert workspace.is_cuda and workspace.is_contiguous()
+        _check(lib().arcq_mx_gemm_ws(_ptr(a_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), M, N, Kp, _ptr(y), dt, ldy,
+                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+    else:
+        _check(lib().arcq_mx_gemm(_ptr(a_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), M, N, Kp, _ptr(y), dt, ldy,
+                                  _stream()))
     return y
 
 
@@ -320,12 +336,17 @@ def prepare_mx_quantize_act(x, perm, S, codes, scales):
     return call
 
 
-def prepare_mx_gemm(a_codes, a_scales, w_codes, w_scales, y):
-    """Same for arcq_mx_gemm."""
+def prepare_mx_gemm(a_codes, a_scales, w_codes, w_scales, y, workspace=None):
+    """Same for arcq_mx_gemm (arcq_mx_gemm_ws when a workspace tensor is given)."""
     M, N, Kp = a_codes.shape[0], w_codes.shape[0], a_codes.shape[1] * 2
-    fn = lib().arcq_mx_gemm
-    args = (_ptr(a_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), M, N, Kp, _ptr(y),
-            DTYPE_F16 if y.dtype == torch.float16 else DTYPE_F32, y.stride(0) if M > 1 else N, _stream())
+    head = (_ptr(a_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), M, N, Kp, _ptr(y),
+            DTYPE_F16 if y.dtype == torch.float16 else DTYPE_F32, y.stride(0) if M > 1 else N)
+    if workspace is not None:
+        fn = lib().arcq_mx_gemm_ws
+        args = head + (_ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    else:
+        fn = lib().arcq_mx_gemm
+        args = head + (_stream(),)
 
     def call():
         _check(fn(*args))

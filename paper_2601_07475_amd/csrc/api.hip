@@ -286,8 +286,9 @@ arcq_status arcq_mx_pack_weight_ex(const void* w, int64_t N, int64_t K, int64_t 
     return mx_quantize_entry(1, "arcq_mx_pack_weight_ex", w, N, K, ldw, perm, S, codes, scales, stream, flags);
 }
 
-arcq_status arcq_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
-                         int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy, void* stream) {
+static arcq_status mx_gemm_entry(const char* name, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                                 const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy,
+                                 bool with_workspace, void* workspace, size_t workspace_bytes, void* stream) {
     clear_error();
     if (M < 0 || N < 0 || M > 0x7FFFFFFF || N > 0x7FFFFFFF)
         return fail(ARCQ_BAD_SHAPE, "M = %lld, N = %lld out of range", (long long)M, (long long)N);
@@ -296,10 +297,43 @@ arcq_status arcq_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const 
     if (y_dtype != ARCQ_DTYPE_F16 && y_dtype != ARCQ_DTYPE_F32) return fail(ARCQ_INVALID_ARG, "y_dtype = %d", y_dtype);
     if (ldy < N) return fail(ARCQ_BAD_SHAPE, "ldy = %lld < N = %lld", (long long)ldy, (long long)N);
     if (M == 0 || N == 0) return ARCQ_OK;
-    if (!a_codes || !a_scales || !w_codes || !w_scales || !y) return fail(ARCQ_INVALID_ARG, "arcq_mx_gemm: null pointer");
-    if (!aligned(a_codes, 4) || !aligned(w_codes, 4)) return fail(ARCQ_BAD_ALIGN, "arcq_mx_gemm: codes must be 4-byte aligned");
-    if (!aligned(y, 4)) return fail(ARCQ_BAD_ALIGN, "arcq_mx_gemm: y must be 4-byte aligned");
-    return launch_mx_gemm(a_codes, a_scales, w_codes, w_scales, M, N, Kp, y, y_dtype, ldy, static_cast<hipStream_t>(stream));
+    if (!a_codes || !a_scales || !w_codes || !w_scales || !y) return fail(ARCQ_INVALID_ARG, "%s: null pointer", name);
+    if (!aligned(a_codes, 4) || !aligned(w_codes, 4)) return fail(ARCQ_BAD_ALIGN, "%s: codes must be 4-byte aligned", name);
+    if (!aligned(y, 4)) return fail(ARCQ_BAD_ALIGN, "%s: y must be 4-byte aligned", name);
+    void* ws = nullptr;
+    if (with_workspace) {
+        const size_t need = mx_gemm_workspace_bytes(M, N, Kp);
+        if (need > 0) {
+            if (!workspace || workspace_bytes < need)
+                return fail(ARCQ_WORKSPACE_TOO_SMALL, "%s: workspace of %zu bytes needed, %zu given", name, need, workspace_bytes);
+            if (!aligned(workspace, 256)) return fail(ARCQ_BAD_ALIGN, "%s: workspace must be 256-byte aligned", name);
+            ws = workspace;
+        }
+    }
+    return launch_mx_gemm(a_codes, a_scales, w_codes, w_scales, M, N, Kp, y, y_dtype, ldy, ws, static_cast<hipStream_t>(stream));
+}
+
+arcq_status arcq_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
+                         int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy, void* stream) {
+    return mx_gemm_entry("arcq_mx_gemm", a_codes, a_scales, w_codes, w_scales, M, N, Kp, y, y_dtype, ldy, false, nullptr, 0, stream);
+}
+
+arcq_status arcq_mx_gemm_workspace_size(int64_t M, int64_t N, int64_t Kp, size_t* bytes) {
+    clear_error();
+    if (M < 0 || N < 0 || M > 0x7FFFFFFF || N > 0x7FFFFFFF)
+        return fail(ARCQ_BAD_SHAPE, "M = %lld, N = %lld out of range", (long long)M, (long long)N);
+    if (Kp <= 0 || (Kp % 32) != 0 || Kp > 2 * (int64_t)ARCQ_MAX_K)
+        return fail(ARCQ_BAD_SHAPE, "K' = %lld: must be a positive multiple of 32, at most %d", (long long)Kp, 2 * ARCQ_MAX_K);
+    if (!bytes) return fail(ARCQ_INVALID_ARG, "null output pointer");
+    *bytes = (M == 0 || N == 0) ? 0 : mx_gemm_workspace_bytes(M, N, Kp);
+    return ARCQ_OK;
+}
+
+arcq_status arcq_mx_gemm_ws(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
+                            int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    return mx_gemm_entry("arcq_mx_gemm_ws", a_codes, a_scales, w_codes, w_scales, M, N, Kp, y, y_dtype, ldy, true, workspace,
+                         workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -701,12 +701,8 @@ arcq_status launch_staged(const uint8_t* a_codes, const uint8_t* a_scales, const
         hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales,
                            w_codes, w_scales, M, N, nbk, 1.0f, partial, (int64_t)N, tiles_m, tiles_n, splits, stride);
         if (arcq_status st = check_launch("gemm_staged_kernel (split K)")) return st;
-        const int vec4 = (N & 3) == 0 && (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
-        const int64_t work = vec4 ? stride / 4 : stride;
-        const int blocks = (int)std::min<int64_t>((work + 255) / 256, 4096);
-        hipLaunchKernelGGL(splitk_reduce_kernel<OutT>, dim3(blocks), dim3(256), 0, stream, partial, splits, stride, M, N,
-                           alpha, y, ldy, vec4);
-        return check_launch("splitk_reduce_kernel");
+        return launch_splitk_reduce(partial, splits, M, N, alpha, y, std::is_same<OutT, _Float16>::value ? ARCQ_DTYPE_F16 : ARCQ_DTYPE_F32,
+                                    ldy, stream);
     }
     auto kern = gemm_staged_kernel<WM, WN, GM, GN, OutT>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1029,6 +1025,21 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
 }
 
 }  // namespace
+
+arcq_status launch_splitk_reduce(const float* partial, int splits, int M, int N, float alpha, void* y, int y_dtype,
+                                 int64_t ldy, hipStream_t stream) {
+    const int64_t stride = (int64_t)M * N;
+    const int vec4 = (N & 3) == 0 && (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
+    const int64_t work = vec4 ? stride / 4 : stride;
+    const int blocks = (int)std::min<int64_t>((work + 255) / 256, 4096);
+    if (y_dtype == ARCQ_DTYPE_F16)
+        hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, stream, partial, splits, stride, M, N,
+                           alpha, static_cast<_Float16*>(y), ldy, vec4);
+    else
+        hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, stream, partial, splits, stride, M, N,
+                           alpha, static_cast<float*>(y), ldy, vec4);
+    return check_launch("splitk_reduce_kernel");
+}
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t Kp) {
     const int splits = split_k(M, N, Kp);

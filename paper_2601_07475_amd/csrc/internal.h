@@ -43,8 +43,13 @@ arcq_status launch_calib_select(const float* colmax, int64_t K, int32_t* perm, i
 // MXFP4 variant (blocks of 32, E8M0 scales, no tensor scale)
 arcq_status launch_mx_quantize(int mode, const void* x, int64_t rows, int64_t K, int64_t ldx, const int32_t* perm,
                                int64_t S, uint8_t* codes, uint8_t* scales, uint32_t flags, hipStream_t stream);
+// workspace: fp32 partial results of a split reduction dimension, or null (never splits)
 arcq_status launch_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                            const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy,
-                           hipStream_t stream);
+                           void* workspace, hipStream_t stream);
+size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t Kp);
+// y = alpha * (partial[0] + partial[1] + ... in index order), partial results fp32 [splits][M][N]
+arcq_status launch_splitk_reduce(const float* partial, int splits, int M, int N, float alpha, void* y, int y_dtype,
+                                 int64_t ldy, hipStream_t stream);
 
 }  // namespace arcq

@@ -66,13 +66,17 @@ template <int WM, int WN, int GM, int GN, typename OutT, bool BF16 = false>
 __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N, int nb,
-    OutT* __restrict__ y, int64_t ldy, int tiles_m, int tiles_n) {
+    OutT* __restrict__ y, int64_t ldy, int tiles_m, int tiles_n, int splits, int64_t split_stride) {
     using C = MxCfg<WM, WN, GM, GN, BF16>;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     // workgroup -> tile: a contiguous run of the tile sequence per XCD, column-major groups of 8 tile rows
+    // With splits > 1 the units of the reduction dimension are cut into `splits` runs: workgroup
+    // blockIdx.x = split * num_tiles + tile accumulates its run and stores an fp32 partial tile at
+    // y + split * split_stride (a reduction kernel adds the partial results in index order).
     const int num_tiles = tiles_m * tiles_n;
-    int pid = blockIdx.x;
+    const int split = (int)blockIdx.x / num_tiles;
+    int pid = (int)blockIdx.x - split * num_tiles;
     if ((num_tiles & 7) == 0) pid = (pid & 7) * (num_tiles >> 3) + (pid >> 3);
     constexpr int GROUP = 8;
     const int group_size = GROUP * tiles_n;
@@ -220,17 +224,19 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
     };
     static_assert(C::NDMA <= 3 * NM, "copies are issued during the first three k-steps of a unit");
 
+    // this workgroup's run of units [u0, u1); copies past the run fetch units the run never uses (in bounds)
+    const int u0 = (int)((int64_t)split * nunit / splits), u1 = (int)((int64_t)(split + 1) * nunit / splits);
 #pragma unroll
     for (int u = 0; u < DIST; ++u)
 #pragma unroll
-        for (int d = 0; d < C::NDMA; ++d) issue_one(d, min(u, nunit - 1), u);
+        for (int d = 0; d < C::NDMA; ++d) issue_one(d, min(u0 + u, nunit - 1), u);
     wait_vmcnt<(DIST - 1) * C::NDMA>();
     wg_barrier();
     read_codes(0, 0, lds);
     read_scales(lds, sa, sw);
     const int nfull = nb >> 3;
-    for (int u = 0; u < nfull; ++u) run_unit(u, std::integral_constant<int, 4>{});
-    if (has_half) run_unit(nfull, std::integral_constant<int, 2>{});
+    for (int u = u0; u < min(u1, nfull); ++u) run_unit(u, std::integral_constant<int, 4>{});
+    if (has_half && u1 == nunit) run_unit(nfull, std::integral_constant<int, 2>{});
     wait_vmcnt<0>();                            // no copy may still be in flight when the LDS is released
 
     const int m0 = wg_m0 + wrow0, n0 = wg_n0 + wcol0;
@@ -241,7 +247,7 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
         store_tile_f16_via_lds<WM, WN>(acc, lds + wave * epilogue_lds_bytes(WN), m0, n0, lane, M, N, 1.0f, y, ldy, vec_ok);
     } else {
         const bool vec_ok = (ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(y) & 15) == 0;
-        store_tile_swapped<WM, WN>(acc, m0, n0, r, h, M, N, 1.0f, y, ldy, vec_ok);
+        store_tile_swapped<WM, WN>(acc, m0, n0, r, h, M, N, 1.0f, y + (int64_t)split * split_stride, ldy, vec_ok);
     }
 }
 
@@ -461,22 +467,63 @@ arcq_status launch_mx_skinny(const uint8_t* a_codes, const uint8_t* a_scales, co
 
 template <int WM, int WN, int GM, int GN, typename OutT, bool BF16 = false>
 arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
-                             const uint8_t* w_scales, int M, int N, int nb, OutT* y, int64_t ldy, hipStream_t stream) {
+                             const uint8_t* w_scales, int M, int N, int nb, OutT* y, int64_t ldy, hipStream_t stream,
+                             int splits = 1, float* partial = nullptr) {
     using C = MxCfg<WM, WN, GM, GN, BF16>;
+    const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
+    if (splits > 1) {
+        // fp32 partial results [splits, M, N] in the workspace, then one pass that adds them
+        auto kern = mx_gemm_staged_kernel<WM, WN, GM, GN, float, BF16>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+        if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
+        hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales,
+                           w_codes, w_scales, M, N, nb, partial, (int64_t)N, tiles_m, tiles_n, splits, (int64_t)M * N);
+        if (arcq_status st = check_launch("mx_gemm_staged_kernel (split K)")) return st;
+        return launch_splitk_reduce(partial, splits, M, N, 1.0f, y, std::is_same<OutT, _Float16>::value ? ARCQ_DTYPE_F16 : ARCQ_DTYPE_F32,
+                                    ldy, stream);
+    }
     auto kern = mx_gemm_staged_kernel<WM, WN, GM, GN, OutT, BF16>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
-    const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales, w_codes,
-                       w_scales, M, N, nb, y, ldy, tiles_m, tiles_n);
+                       w_scales, M, N, nb, y, ldy, tiles_m, tiles_n, 1, (int64_t)0);
     return check_launch("mx_gemm_staged_kernel");
+}
+
+// Number of runs the units of the reduction dimension are cut into when the caller provides a workspace (1: no
+// split): a function of the shape alone.  Only the 128 x 128 tiles of few-tile problems split; the cost, in
+// microseconds, is rounds of workgroups over the 256 CUs times the units of a run at about 0.65 us a unit, plus,
+// when split, the write and read of the fp32 partial results at about 3 TB/s and 5.5 us for the shorter runs'
+// pipeline fill and the second launch (fitted to measurements over N = 2048 .. 8192, K' = 4352 .. 29696).
+int mx_split_k(int64_t M, int64_t N, int64_t Kp) {
+    const int64_t nb = Kp >> 5;
+    if ((nb & 3) != 0) return 1;
+    const bool streaming = M <= 32 ? N * Kp < 200000000 : M <= 64 && N < 8192;
+    if (streaming) return 1;
+    if (((M + 255) / 256) * ((N + 255) / 256) >= 256 || ((M + 127) / 128) * ((N + 255) / 256) >= 192) return 1;
+    const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    const int64_t nunit = (nb + 7) >> 3;
+    const int64_t max_splits = std::min<int64_t>(8, nunit / 2);
+    int best = 1;
+    double best_cost = 0.0;
+    for (int64_t sp = 1; sp <= max_splits; ++sp) {
+        const double rounds = (double)((tiles * sp + 255) / 256);
+        double cost = rounds * (double)((nunit + sp - 1) / sp) * 0.65;
+        if (sp > 1) cost += (double)sp * (double)M * (double)N * 8.0 / 3.0e6 + 5.5;
+        if (sp == 1 || cost < best_cost) {
+            best = (int)sp;
+            best_cost = cost;
+        }
+    }
+    return best;
 }
 
 template <typename OutT>
 arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                             const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, OutT* y, int64_t ldy,
-                            hipStream_t stream) {
+                            float* workspace, hipStream_t stream) {
     const int nb = (int)(Kp >> 5);
     const bool offsets_fit = (uint64_t)M * (uint64_t)nb * 16 < 0xFFFF0000ull && (uint64_t)N * (uint64_t)nb * 16 < 0xFFFF0000ull;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
@@ -510,7 +557,8 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
         const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
         if (t128x256 >= 192)
             return launch_mx_staged<2, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
-        return launch_mx_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
+        return launch_mx_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream,
+                                            workspace ? mx_split_k(M, N, Kp) : 1, workspace);
     }
     dim3 grid((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128));
     hipLaunchKernelGGL(mx_gemm_direct_kernel<OutT>, grid, dim3(256), 0, stream, a_codes, a_scales, w_codes, w_scales,
@@ -534,12 +582,18 @@ arcq_status launch_ref_gemm_bf16(const void* x, const void* w, int64_t M, int64_
     return launch_mx_staged<2, 2, 2, 2, _Float16, true>(a, nullptr, b, nullptr, (int)M, (int)N, nb, y, ldy, stream);
 }
 
+size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t Kp) {
+    const int splits = mx_split_k(M, N, Kp);
+    return splits > 1 ? (size_t)splits * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
 arcq_status launch_mx_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                            const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy,
-                           hipStream_t stream) {
+                           void* workspace, hipStream_t stream) {
+    float* ws = static_cast<float*>(workspace);
     if (y_dtype == ARCQ_DTYPE_F16)
-        return launch_mx_typed<_Float16>(a_codes, a_scales, w_codes, w_scales, M, N, Kp, static_cast<_Float16*>(y), ldy, stream);
-    return launch_mx_typed<float>(a_codes, a_scales, w_codes, w_scales, M, N, Kp, static_cast<float*>(y), ldy, stream);
+        return launch_mx_typed<_Float16>(a_codes, a_scales, w_codes, w_scales, M, N, Kp, static_cast<_Float16*>(y), ldy, ws, stream);
+    return launch_mx_typed<float>(a_codes, a_scales, w_codes, w_scales, M, N, Kp, static_cast<float*>(y), ldy, ws, stream);
 }
 
 }  // namespace arcq

@@ -63,7 +63,7 @@ def test_nvfp4_step_replays_bit_identically(M, K, N, S):
 
 def test_rmsnorm_and_mxfp4_steps_replay_bit_identically():
     say("graph capture of rmsnorm_quantize_act + gemm and of the MXFP4 step")
-    M, K, N, S = 130, 2048, 512, 128
+    M, K, N, S = 130, 8192, 512, 128         # long enough for the MXFP4 GEMM to split K' when given a workspace
     Xn, gamma, perm_n, sT = norm_case(M, K, S, seed=71)
     c = rand_case(M, K, N, S, seed=72)
     inputs = [dev(norm_case(M, K, S, seed=73 + i)[0]) for i in range(4)]
@@ -80,17 +80,19 @@ def test_rmsnorm_and_mxfp4_steps_replay_bit_identically():
     Y = torch.empty((M, N), dtype=torch.float16, device="cuda")
     Ym = torch.empty((M, N), dtype=torch.float32, device="cuda")
     ws = torch.empty(max(B.arcq_gemm_workspace_size(M, N, Kp), 1), dtype=torch.uint8, device="cuda")
+    assert B.arcq_mx_gemm_workspace_size(M, N, Kp) > 0
+    mws = torch.empty(B.arcq_mx_gemm_workspace_size(M, N, Kp), dtype=torch.uint8, device="cuda")
 
     def eager():
         B.arcq_rmsnorm_quantize_act(X, g_, 1e-5, perm, S, sT, codes=ac, scales=asc)
         B.arcq_gemm(ac, asc, sT, wc, wsc, sTw, y=Y, workspace=ws)
         B.arcq_mx_quantize_act(X, perm, S, codes=mac, scales=masc)
-        B.arcq_mx_gemm(mac, masc, mwc, mwsc, y=Ym)
+        B.arcq_mx_gemm(mac, masc, mwc, mwsc, y=Ym, workspace=mws)
 
     def capture():
         B.prepare_rmsnorm_quantize_act(X, g_, 1e-5, perm, S, sT, ac, asc)()
         B.prepare_gemm(ac, asc, sT, wc, wsc, sTw, Y, ws)()
         B.prepare_mx_quantize_act(X, perm, S, mac, masc)()
-        B.prepare_mx_gemm(mac, masc, mwc, mwsc, Ym)()
+        B.prepare_mx_gemm(mac, masc, mwc, mwsc, Ym, mws)()
 
     _replays_match(capture, eager, [ac, asc, Y, mac, masc, Ym], lambda i: X.copy_(inputs[i]))

@@ -630,3 +630,38 @@ def test_ref_gemm_bf16_against_fp64(M, N, K):
     Y = B.arcq_ref_gemm_bf16(x.cuda(), w.cuda()).float().cpu().numpy()
     Yref = x.double().numpy() @ w.double().numpy().T
     assert norm_err(Y, Yref) <= GEMM_TOL_F16
+
+
+@pytest.mark.parametrize("M,N,K,S", [(200, 260, 8192, 512), (130, 129, 4192, 32), (384, 1000, 6144, 0), (100, 300, 14336, 256)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+def test_mx_gemm_with_workspace_splits_the_reduction(M, N, K, S, dtype):
+    """Few-tile problems with a long K' on arcq_mx_gemm_ws: 2 to 8 runs (the second ends with a half unit), against the
+    oracle and against the plain entry point (same products, another order of the fp32 additions)."""
+    say(f"mx_gemm_ws parity M={M} N={N} K={K} S={S} {dtype}")
+    c = rand_case(M, K, N, S, seed=870 + M + N)
+    ac, asc = MX.quantize_act(c["X"], c["perm"], S)
+    wc, wsc = MX.pack_weight(c["W"], c["perm"], S)
+    Yref = MX.gemm(ac, asc, wc, wsc)
+    need = B.arcq_mx_gemm_workspace_size(M, N, K + S)
+    assert need > 0 and need % (M * N * 4) == 0 and 2 <= need // (M * N * 4) <= 8
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    Y = B.arcq_mx_gemm(dev(ac), dev(asc), dev(wc), dev(wsc), out_dtype=dtype, workspace=ws)
+    Y1 = B.arcq_mx_gemm(dev(ac), dev(asc), dev(wc), dev(wsc), out_dtype=dtype)
+    torch.cuda.synchronize()
+    tol = GEMM_TOL_F16 if dtype == torch.float16 else GEMM_TOL_F32
+    assert norm_err(Y.float().cpu().numpy(), Yref) <= tol
+    assert norm_err(Y.float().cpu().numpy(), Y1.float().cpu().numpy().astype(np.float64)) <= tol
+    with pytest.raises(B.ArcqError):
+        B.arcq_mx_gemm(dev(ac), dev(asc), dev(wc), dev(wsc), out_dtype=dtype, workspace=ws[: need - 256])
+
+
+def test_mx_gemm_workspace_is_not_needed_where_nothing_splits():
+    say("mx_gemm_ws where the plain kernels run")
+    for M, N, Kp in ((16, 4096, 4352), (2048, 4096, 4352), (300, 260, 96), (64, 300, 8192)):
+        assert B.arcq_mx_gemm_workspace_size(M, N, Kp) == 0
+    c = rand_case(40, 256, 96, 32, seed=5)
+    ac, asc = MX.quantize_act(c["X"], c["perm"], 32)
+    wc, wsc = MX.pack_weight(c["W"], c["perm"], 32)
+    a = B.arcq_mx_gemm(dev(ac), dev(asc), dev(wc), dev(wsc), workspace=torch.empty(0, dtype=torch.uint8, device="cuda"))
+    b = B.arcq_mx_gemm(dev(ac), dev(asc), dev(wc), dev(wsc))
+    assert torch.equal(a, b)

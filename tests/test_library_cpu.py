@@ -204,3 +204,20 @@ def test_ref_gemm_bf16_argument_errors():
     assert L.arcq_ref_gemm_bf16(None, FAKE, 8, 8, 64, FAKE, 8, None) == B.INVALID_ARG
     assert L.arcq_ref_gemm_bf16(ctypes.c_void_p(0x10008), FAKE, 8, 8, 64, FAKE, 8, None) == B.BAD_ALIGN
     assert L.arcq_ref_gemm_bf16(FAKE, FAKE, 0, 8, 64, FAKE, 8, None) == B.OK                # empty
+
+
+def test_mx_gemm_workspace_entry_points():
+    L = B.lib()
+    n = ctypes.c_size_t(7)
+    assert L.arcq_mx_gemm_workspace_size(16, 4096, 4352, ctypes.byref(n)) == B.OK and n.value == 0       # weight-streaming kernel
+    assert L.arcq_mx_gemm_workspace_size(2048, 4096, 4352, ctypes.byref(n)) == B.OK and n.value == 0     # enough tiles
+    assert L.arcq_mx_gemm_workspace_size(256, 4096, 14592, ctypes.byref(n)) == B.OK
+    assert n.value % (256 * 4096 * 4) == 0 and 2 <= n.value // (256 * 4096 * 4) <= 8
+    need = n.value
+    assert L.arcq_mx_gemm_workspace_size(256, 4096, 48, ctypes.byref(n)) == B.BAD_SHAPE
+    assert L.arcq_mx_gemm_workspace_size(256, 4096, 14592, None) == B.INVALID_ARG
+    args = (FAKE, FAKE, FAKE, FAKE, 256, 4096, 14592, FAKE, B.DTYPE_F16, 4096)
+    assert L.arcq_mx_gemm_ws(*args, None, 0, None) == B.WORKSPACE_TOO_SMALL
+    assert L.arcq_mx_gemm_ws(*args, FAKE, need - 1, None) == B.WORKSPACE_TOO_SMALL
+    assert L.arcq_mx_gemm_ws(*args, ctypes.c_void_p(0x10010), need, None) == B.BAD_ALIGN
+    assert L.arcq_mx_gemm_ws(FAKE, FAKE, FAKE, FAKE, 256, 4096, 14592, FAKE, 7, 4096, FAKE, need, None) == B.INVALID_ARG
