@@ -49,11 +49,11 @@ PEAK_MFMA_FP4_TFLOPS = 10100.0 # MI355X dense fp4 MFMA (the MXFP4 variant's GEMM
 # profiles/), scaled by the factor the same counters read for a plain copy of known size.
 # workload -> kernel -> bytes; None where not measured.
 MEASURED_TRAFFIC = {
-    "c2_llama8b_q": {"arcq_gemm": 57334051, "arcq_quantize_act": 22006789, "arcq_rmsnorm_quantize_act": 22096896, "arcq_mx_quantize_act": 21727232, "arcq_mx_gemm": 54879243},
-    "c4_qwen32b_mlp": {"arcq_gemm": 779679605, "arcq_quantize_act": 55196810, "arcq_rmsnorm_quantize_act": 55242245, "arcq_mx_quantize_act": 54475079, "arcq_mx_gemm": 735563373},
-    "c5_llama70b_down": {"arcq_gemm": 1782204367, "arcq_quantize_act": 621205442, "arcq_rmsnorm_quantize_act": 622437157, "arcq_mx_quantize_act": 612800491, "arcq_mx_gemm": 1694875754},
-    "c3a_llama8b_up": {"arcq_gemm": 36219818, "arcq_quantize_act": 353792, "arcq_rmsnorm_quantize_act": 443904, "arcq_mx_quantize_act": 334336, "arcq_mx_gemm": 34167573},
-    "c3b_llama8b_down": {"arcq_gemm": 35089088, "arcq_quantize_act": 1101312, "arcq_rmsnorm_quantize_act": 1355264, "arcq_mx_quantize_act": 1076736, "arcq_mx_gemm": 32989406},
+    "c2_llama8b_q": {"arcq_gemm": 57350812, "arcq_quantize_act": 22006789, "arcq_rmsnorm_quantize_act": 22096896, "arcq_mx_quantize_act": 21727232, "arcq_mx_gemm": 54907910},
+    "c4_qwen32b_mlp": {"arcq_gemm": 779865347, "arcq_quantize_act": 55168145, "arcq_rmsnorm_quantize_act": 55242134, "arcq_mx_quantize_act": 54472568, "arcq_mx_gemm": 735300181},
+    "c5_llama70b_down": {"arcq_gemm": 1782181517, "arcq_quantize_act": 621149182, "arcq_rmsnorm_quantize_act": 622470456, "arcq_mx_quantize_act": 612794081, "arcq_mx_gemm": 1694914656},
+    "c3a_llama8b_up": {"arcq_gemm": 36275510, "arcq_quantize_act": 353792, "arcq_rmsnorm_quantize_act": 443904, "arcq_mx_quantize_act": 334336, "arcq_mx_gemm": 34061503},
+    "c3b_llama8b_down": {"arcq_gemm": 35078642, "arcq_quantize_act": 1101312, "arcq_rmsnorm_quantize_act": 1355264, "arcq_mx_quantize_act": 1076736, "arcq_mx_gemm": 32992742},
 }
 
 
