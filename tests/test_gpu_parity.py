@@ -4,6 +4,9 @@ Bars: codes and scale bytes bit-exact; GEMM within 1e-3 of the fp64 oracle in th
 max error  max_ij |Y - Yref| / max(|Yref_ij|, rms(Yref))  (element-wise relative error is
 unbounded at cancellation zeros), fp32 accumulate.
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 import torch
@@ -352,60 +355,111 @@ def test_gemm_strided_output_and_guard():
 
 
 # --------------------------------------------------------------------------------------
-def run_full_config(name, sample_rows, sample_cols, full_quant):
-    """The whole hot path at a configuration's full size, as the benchmark launches it; the oracle
-    checks all of it where it can finish in seconds, otherwise sampled rows of X / W and the
-    corresponding entries of Y."""
-    wl = wk.WORKLOADS[name]
-    say(f"full config {name}: M={wl.M} K={wl.K} N={wl.N} S={wl.S}")
-    c = wk.make_case(wl)
-    X, W, perm, S = c["X"], c["W"], c["perm"], c["S"]
-    permd = dev(perm)
-    say("   gpu: quantize_act, pack_weight, gemm")
-    ac, asc = B.arcq_quantize_act(dev(X), permd, S, c["sT_x"])
-    wc, wsc = B.arcq_pack_weight(dev(W), permd, S, c["sT_w"])
-    Y = B.arcq_gemm(ac, asc, c["sT_x"], wc, wsc, c["sT_w"], out_dtype=torch.float16)
+# Every configuration at its full size, launched as the benchmark launches it, and compared with the oracle in
+# full: every code byte and scale byte of X and of W, and every element of Y (fp16 and fp32 output) against the
+# fp64 product of the oracle's own packed operands.  The oracle works through the rows in chunks of about 2^18
+# elements (its temporaries stay in the caches) on a pool of threads (numpy releases the interpreter lock
+# inside its loops); chunking by rows changes nothing in what it computes, since every row is independent.
+ORACLE_THREADS = min(16, os.cpu_count() or 1)
+FULL_CONFIGS = ["c1_tiny", "c2_llama8b_q", "c3a_llama8b_up", "c3b_llama8b_down", "c4_qwen32b_mlp", "c5_llama70b_down"]
+
+
+def oracle_by_rows(fn, T, chunk_elems=1 << 18):
+    """fn(rows of T) -> tuple of arrays with one row per input row, evaluated chunk by chunk and concatenated."""
+    step = max(1, chunk_elems // T.shape[1])
+    with ThreadPoolExecutor(ORACLE_THREADS) as ex:
+        parts = list(ex.map(lambda r0: fn(T[r0:r0 + step]), range(0, T.shape[0], step)))
+    return tuple(np.concatenate([p[i] for p in parts]) for i in range(len(parts[0])))
+
+
+class FullConfig:
+    def __init__(self, name):
+        wl = self.wl = wk.WORKLOADS[name]
+        say(f"full config {name}: M={wl.M} K={wl.K} N={wl.N} S={wl.S}: inputs")
+        self.c = wk.make_case(wl)
+        self._act = self._wgt = self._yref = self._gpu = None
+
+    def gpu(self):
+        """The HIP path's packed operands (device tensors), computed once."""
+        if self._gpu is None:
+            c = self.c
+            permd = dev(c["perm"])
+            ac, asc = B.arcq_quantize_act(dev(c["X"]), permd, c["S"], c["sT_x"])
+            wc, wsc = B.arcq_pack_weight(dev(c["W"]), permd, c["S"], c["sT_w"])
+            torch.cuda.synchronize()
+            self._gpu = (ac, asc, wc, wsc)
+        return self._gpu
+
+    def oracle_act(self):
+        if self._act is None:
+            c = self.c
+            say("   oracle: quantize_act on every row")
+            self._act = oracle_by_rows(lambda x: A.quantize_act(x, c["perm"], c["S"], c["sT_x"]), c["X"])
+        return self._act
+
+    def oracle_wgt(self):
+        if self._wgt is None:
+            c = self.c
+            say("   oracle: pack_weight on every row")
+            self._wgt = oracle_by_rows(lambda w: A.pack_weight(w, c["perm"], c["S"], c["sT_w"]), c["W"])
+        return self._wgt
+
+    def oracle_y(self):
+        """eq. (2) in fp64 on the ORACLE's packed operands, all M x N entries."""
+        if self._yref is None:
+            c, wl = self.c, self.wl
+            (oac, oasc), (owc, owsc) = self.oracle_act(), self.oracle_wgt()
+            say("   oracle: fp64 dequantize + product, every entry")
+            step = max(1, (1 << 18) // (wl.K + wl.S))
+            with ThreadPoolExecutor(ORACLE_THREADS) as ex:
+                Wd = np.concatenate(list(ex.map(
+                    lambda r0: A.dequantize(owc[r0:r0 + step], owsc[r0:r0 + step], c["sT_w"]), range(0, wl.N, step))))
+            Y = np.empty((wl.M, wl.N))
+            for r0 in range(0, wl.M, 1024):
+                Y[r0:r0 + 1024] = A.dequantize(oac[r0:r0 + 1024], oasc[r0:r0 + 1024], c["sT_x"]) @ Wd.T
+            self._yref = Y
+        return self._yref
+
+
+@pytest.fixture(scope="module", params=FULL_CONFIGS)
+def full(request):
+    fc = FullConfig(request.param)
+    yield fc
+    fc.__dict__.clear()
+    torch.cuda.empty_cache()
+
+
+def test_full_size_activation_bytes(full):
+    ac, asc, _, _ = full.gpu()
+    oac, oasc = full.oracle_act()
+    assert_same_bytes(asc.cpu().numpy(), oasc, "activation scales")
+    assert_same_bytes(ac.cpu().numpy(), oac, "activation codes")
+
+
+def test_full_size_weight_bytes(full):
+    _, _, wc, wsc = full.gpu()
+    owc, owsc = full.oracle_wgt()
+    assert_same_bytes(wsc.cpu().numpy(), owsc, "weight scales")
+    assert_same_bytes(wc.cpu().numpy(), owc, "weight codes")
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+def test_full_size_gemm_every_entry(full, dtype):
+    c = full.c
+    ac, asc, wc, wsc = full.gpu()
+    Y = B.arcq_gemm(ac, asc, c["sT_x"], wc, wsc, c["sT_w"], out_dtype=dtype)
     torch.cuda.synchronize()
-    rng = np.random.default_rng(wl.seed)
-    rows = np.arange(wl.M) if full_quant else np.sort(rng.choice(wl.M, min(sample_rows, wl.M), replace=False))
-    cols = np.arange(wl.N) if full_quant else np.sort(rng.choice(wl.N, min(sample_cols, wl.N), replace=False))
-    say(f"   oracle: {len(rows)} rows of X, {len(cols)} rows of W")
-    oac, oasc = A.quantize_act(X[rows], perm, S, c["sT_x"])
-    owc, owsc = [], []
-    for i in range(0, len(cols), 512):                   # chunked: the oracle's temporaries are 8x fp64
-        cc, ss = A.pack_weight(W[cols[i:i + 512]], perm, S, c["sT_w"])
-        owc.append(cc); owsc.append(ss)
-    owc, owsc = np.concatenate(owc), np.concatenate(owsc)
-    assert_same_bytes(asc.cpu().numpy()[rows], oasc, "activation scales")
-    assert_same_bytes(ac.cpu().numpy()[rows], oac, "activation codes")
-    assert_same_bytes(wsc.cpu().numpy()[cols], owsc, "weight scales")
-    assert_same_bytes(wc.cpu().numpy()[cols], owc, "weight codes")
-    Yref = A.gemm(oac, oasc, c["sT_x"], owc, owsc, c["sT_w"])
-    Yg = Y.cpu().numpy()[np.ix_(rows, cols)]
-    err = norm_err(Yg, Yref)
-    say(f"   gemm normalised max error {err:.3e}")
-    assert err <= GEMM_TOL_F16
-
-
-def test_config1_tiny_full():
-    run_full_config("c1_tiny", 0, 0, True)
-
-
-def test_config2_llama8b_qproj_full():
-    run_full_config("c2_llama8b_q", 0, 0, True)
-
-
-def test_config3_llama8b_mlp_decode_full():
-    run_full_config("c3a_llama8b_up", 16, 2048, False)
-    run_full_config("c3b_llama8b_down", 16, 1024, False)
-
-
-def test_config4_qwen32b_mlp_sampled():
-    run_full_config("c4_qwen32b_mlp", 96, 1024, False)
-
-
-def test_config5_llama70b_down_sampled():
-    run_full_config("c5_llama70b_down", 48, 384, False)
+    Yref = full.oracle_y()
+    rms = max(float(np.sqrt(np.mean(Yref ** 2))), 1e-300)
+    err, worst = 0.0, None
+    for r0 in range(0, full.wl.M, 512):                       # row chunks only bound the temporaries
+        ref = Yref[r0:r0 + 512]
+        e = np.abs(Y[r0:r0 + 512].double().cpu().numpy() - ref) / np.maximum(np.abs(ref), rms)
+        i = np.unravel_index(np.argmax(e), e.shape)
+        if e[i] > err:
+            err, worst = float(e[i]), (r0 + int(i[0]), int(i[1]))
+    say(f"   {full.wl.name} {dtype}: normalised max error {err:.3e} at {worst} over {Yref.size} entries")
+    assert err <= (GEMM_TOL_F16 if dtype == torch.float16 else GEMM_TOL_F32)
 
 
 # --------------------------------------------------------------------------------------
