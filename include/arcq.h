@@ -165,6 +165,26 @@ arcq_status arcq_gemm(const uint8_t* a_codes, const uint8_t* a_scales, float a_t
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * arcq_gemm for callers that cannot allocate device memory for a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments minus the workspace, same kernels, same
+ * result bit for bit.  The fp32 partial results of a split reduction dimension go to a buffer of
+ * ARCQ_NOALLOC_SCRATCH_BYTES that is part of the library image (every GPU the library runs on holds its own
+ * copy until the process ends); the call allocates and frees nothing.
+ *   - Shapes whose arcq_gemm_workspace_size exceeds ARCQ_NOALLOC_SCRATCH_BYTES are rejected with
+ *     ARCQ_WORKSPACE_TOO_SMALL (use arcq_gemm with a workspace of the caller); checked before any HIP call.
+ *   - The device of `stream` must be the calling thread's current device.  The first call on a device that needs
+ *     scratch looks the buffer's address up once (hipGetSymbolAddress); make that call outside a graph capture.
+ *   - All calls on one GPU share the buffer: calls that may overlap (different streams, or graphs replayed
+ *     concurrently) race on it; order them.  Nothing in it has to start at zero (every partial result is written
+ *     before it is read), and its contents are undefined afterwards.
+ */
+#define ARCQ_NOALLOC_SCRATCH_BYTES (32u << 20)
+arcq_status arcq_gemm_noalloc(const uint8_t* a_codes, const uint8_t* a_scales, float a_tensor_scale,
+                              const uint8_t* w_codes, const uint8_t* w_scales, float w_tensor_scale,
+                              int64_t M, int64_t N, int64_t Kp,
+                              void* y, int y_dtype, int64_t ldy, void* stream);
+
+/*
  * Debug helper: checks on the device that perm[0..K-1] is a permutation of 0..K-1
  * (the calibration output of Section 3.2 "Adaptive Outlier Identification").
  * flags: device scratch, K bytes.  *result_host is written after the stream has been

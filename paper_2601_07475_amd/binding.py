@@ -42,6 +42,7 @@ SIGNATURES = {
     "arcq_gemm_workspace_size": (ctypes.c_int, [_i64, _i64, _i64, ctypes.POINTER(_sz)]),
     "arcq_gemm": (ctypes.c_int, [_vp, _vp, _f32, _vp, _vp, _f32, _i64, _i64, _i64, _vp, ctypes.c_int, _i64,
                                  _vp, _sz, _vp]),
+    "arcq_gemm_noalloc": (ctypes.c_int, [_vp, _vp, _f32, _vp, _vp, _f32, _i64, _i64, _i64, _vp, ctypes.c_int, _i64, _vp]),
     "arcq_probe_mfma_f16": (ctypes.c_int, [ctypes.c_int, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
     "arcq_probe_mfma_fp4": (ctypes.c_int, [ctypes.c_int, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
     "arcq_ref_gemm_bf16": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp]),
@@ -185,6 +186,26 @@ def arcq_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_sca
                            _ptr(w_codes), _ptr(w_scales), float(w_tensor_scale), M, N, Kp,
                            _ptr(y), DTYPE_F16 if y.dtype == torch.float16 else DTYPE_F32, ldy,
                            _ptr(workspace) if workspace is not None else None, ws_bytes, _stream()))
+    return y
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def arcq_gemm_noalloc(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, y):
+    """arcq_gemm without a workspace argument: split-K partial results go to the library's built-in scratch.
+    The output tensor y [M, N] (fp16 or fp32) is the caller's; nothing is allocated here or in the library."""
+    for t in (a_codes, a_scales, w_codes, w_scales):
+        assert t.is_cuda and t.dtype == torch.uint8 and t.is_contiguous()
+    M, N = a_codes.shape[0], w_codes.shape[0]
+    Kp = a_codes.shape[1] * 2
+    if w_codes.shape[1] * 2 != Kp or a_scales.shape != (M, Kp // 16) or w_scales.shape != (N, Kp // 16):
+        raise ArcqError(BAD_SHAPE, "operand shapes disagree on K'")
+    assert y.shape == (M, N) and y.stride(1) == 1 and y.dtype in (torch.float16, torch.float32)
+    ldy = y.stride(0) if M > 1 else max(N, y.stride(0))
+    _check(lib().arcq_gemm_noalloc(_ptr(a_codes), _ptr(a_scales), float(a_tensor_scale),
+                                   _ptr(w_codes), _ptr(w_scales), float(w_tensor_scale), M, N, Kp,
+                                   _ptr(y), DTYPE_F16 if y.dtype == torch.float16 else DTYPE_F32, ldy, _stream()))
     return y
 
 

@@ -171,20 +171,33 @@ arcq_status arcq_gemm_workspace_size(int64_t M, int64_t N, int64_t Kp, size_t* b
     return ARCQ_OK;
 }
 
-arcq_status arcq_gemm(const uint8_t* a_codes, const uint8_t* a_scales, float a_tensor_scale,
-                      const uint8_t* w_codes, const uint8_t* w_scales, float w_tensor_scale,
-                      int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy,
-                      void* workspace, size_t workspace_bytes, void* stream) {
-    clear_error();
+// Validation shared by arcq_gemm and arcq_gemm_noalloc; *run = false when there is nothing to launch.
+static arcq_status check_gemm_args(const char* who, const uint8_t* a_codes, const uint8_t* a_scales, float a_tensor_scale,
+                                   const uint8_t* w_codes, const uint8_t* w_scales, float w_tensor_scale,
+                                   int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy, bool* run) {
+    *run = false;
     if (arcq_status st = check_gemm_shape(M, N, Kp)) return st;
     if (y_dtype != ARCQ_DTYPE_F16 && y_dtype != ARCQ_DTYPE_F32) return fail(ARCQ_INVALID_ARG, "y_dtype = %d", y_dtype);
     if (ldy < N) return fail(ARCQ_BAD_SHAPE, "ldy = %lld < N = %lld", (long long)ldy, (long long)N);
     if (arcq_status st = check_scale(a_tensor_scale, "a_tensor_scale")) return st;
     if (arcq_status st = check_scale(w_tensor_scale, "w_tensor_scale")) return st;
     if (M == 0 || N == 0) return ARCQ_OK;
-    if (!a_codes || !a_scales || !w_codes || !w_scales || !y) return fail(ARCQ_INVALID_ARG, "arcq_gemm: null pointer");
-    if (!aligned(a_codes, 8) || !aligned(w_codes, 8)) return fail(ARCQ_BAD_ALIGN, "arcq_gemm: codes must be 8-byte aligned");
-    if (!aligned(y, 4)) return fail(ARCQ_BAD_ALIGN, "arcq_gemm: y must be 4-byte aligned");
+    if (!a_codes || !a_scales || !w_codes || !w_scales || !y) return fail(ARCQ_INVALID_ARG, "%s: null pointer", who);
+    if (!aligned(a_codes, 8) || !aligned(w_codes, 8)) return fail(ARCQ_BAD_ALIGN, "%s: codes must be 8-byte aligned", who);
+    if (!aligned(y, 4)) return fail(ARCQ_BAD_ALIGN, "%s: y must be 4-byte aligned", who);
+    *run = true;
+    return ARCQ_OK;
+}
+
+arcq_status arcq_gemm(const uint8_t* a_codes, const uint8_t* a_scales, float a_tensor_scale,
+                      const uint8_t* w_codes, const uint8_t* w_scales, float w_tensor_scale,
+                      int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    clear_error();
+    bool run = false;
+    if (arcq_status st = check_gemm_args("arcq_gemm", a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale,
+                                         M, N, Kp, y, y_dtype, ldy, &run)) return st;
+    if (!run) return ARCQ_OK;
     const size_t need = gemm_workspace_bytes(M, N, Kp);
     if (need > 0) {
         if (!workspace || workspace_bytes < need)
@@ -195,6 +208,27 @@ arcq_status arcq_gemm(const uint8_t* a_codes, const uint8_t* a_scales, float a_t
     const float alpha = a_tensor_scale * w_tensor_scale;
     return launch_gemm(a_codes, a_scales, w_codes, w_scales, M, N, Kp, alpha, y, y_dtype, ldy, workspace,
                        workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+arcq_status arcq_gemm_noalloc(const uint8_t* a_codes, const uint8_t* a_scales, float a_tensor_scale,
+                              const uint8_t* w_codes, const uint8_t* w_scales, float w_tensor_scale,
+                              int64_t M, int64_t N, int64_t Kp, void* y, int y_dtype, int64_t ldy, void* stream) {
+    clear_error();
+    bool run = false;
+    if (arcq_status st = check_gemm_args("arcq_gemm_noalloc", a_codes, a_scales, a_tensor_scale, w_codes, w_scales,
+                                         w_tensor_scale, M, N, Kp, y, y_dtype, ldy, &run)) return st;
+    const size_t need = (M == 0 || N == 0) ? 0 : gemm_workspace_bytes(M, N, Kp);
+    if (need > (size_t)ARCQ_NOALLOC_SCRATCH_BYTES)
+        return fail(ARCQ_WORKSPACE_TOO_SMALL,
+                    "arcq_gemm_noalloc: this shape needs %zu bytes of scratch, the built-in buffer holds %zu; "
+                    "call arcq_gemm with a workspace of the caller", need, (size_t)ARCQ_NOALLOC_SCRATCH_BYTES);
+    if (!run) return ARCQ_OK;
+    void* ws = nullptr;
+    if (need > 0)
+        if (arcq_status st = gemm_scratch_pointer(&ws)) return st;
+    const float alpha = a_tensor_scale * w_tensor_scale;
+    return launch_gemm(a_codes, a_scales, w_codes, w_scales, M, N, Kp, alpha, y, y_dtype, ldy, ws, need,
+                       static_cast<hipStream_t>(stream));
 }
 
 arcq_status arcq_check_perm(const int32_t* perm, int64_t K, uint8_t* flags, int* result_host, void* stream) {

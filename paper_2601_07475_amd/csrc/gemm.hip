@@ -19,6 +19,7 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <type_traits>
 
@@ -1044,6 +1045,34 @@ arcq_status launch_splitk_reduce(const float* partial, int splits, int M, int N,
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t Kp) {
     const int splits = split_k(M, N, Kp);
     return splits > 1 ? (size_t)splits * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scratch memory of arcq_gemm_noalloc: the fp32 partial results of a split reduction dimension for
+// callers that cannot allocate a workspace.  Every GPU the library runs on holds its own copy of this
+// array, at its own address, until the process ends.  In host code the array's name is only a stand-in
+// for hipGetSymbolAddress; launches get the per-device address kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[ARCQ_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+}  // namespace
+
+// Device address of `scratch` on the current device; looked up once per device.
+arcq_status gemm_scratch_pointer(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ARCQ_HIP_ERROR, "device index %d beyond the %d this library keeps scratch for", dev, kMaxDevices);
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(ARCQ_HIP_ERROR, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        g_scratch_ptr[dev].store(p, std::memory_order_release);     // the same value from whichever thread gets here first
+    }
+    *out = p;
+    return ARCQ_OK;
 }
 
 arcq_status launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales,

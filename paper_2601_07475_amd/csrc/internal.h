@@ -23,6 +23,8 @@ arcq_status launch_quantize(int mode, const void* x, int64_t rows, int64_t K, in
                             hipStream_t stream);
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t Kp);
+// device address, on the current device, of the library's built-in scratch (ARCQ_NOALLOC_SCRATCH_BYTES)
+arcq_status gemm_scratch_pointer(void** out);
 arcq_status launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
                         const uint8_t* w_codes, const uint8_t* w_scales,
                         int64_t M, int64_t N, int64_t Kp, float alpha,

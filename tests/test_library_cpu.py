@@ -119,6 +119,22 @@ def test_gemm_argument_errors():
     assert B.lib().arcq_gemm_workspace_size(2048, 4096, 4352, ctypes.byref(n)) == B.OK and n.value == 0
 
 
+def test_gemm_noalloc_argument_errors_and_scratch_limit():
+    """The entry point for callers that cannot allocate: the rules of arcq_gemm, and shapes whose partial results
+    exceed the built-in scratch are turned away before anything touches the GPU."""
+    ga = lambda ac=FAKE, M=4, N=8, Kp=64, y=FAKE, dt=0, ldy=8, sa=1.0: B.lib().arcq_gemm_noalloc(
+        ac, FAKE, sa, FAKE, FAKE, 1.0, M, N, Kp, y, dt, ldy, None)
+    assert ga(Kp=40) == B.BAD_SHAPE and ga(M=-1) == B.BAD_SHAPE and ga(ldy=4) == B.BAD_SHAPE
+    assert ga(dt=7) == B.INVALID_ARG and ga(sa=0.0) == B.INVALID_ARG and ga(ac=None) == B.INVALID_ARG
+    assert ga(ac=ODD) == B.BAD_ALIGN and ga(y=ctypes.c_void_p(0x10002)) == B.BAD_ALIGN
+    assert ga(M=0, ac=None, y=None) == B.OK
+    n = ctypes.c_size_t(0)
+    assert B.lib().arcq_gemm_workspace_size(384, 4096, 65536, ctypes.byref(n)) == B.OK
+    assert n.value > B.NOALLOC_SCRATCH_BYTES == 32 << 20
+    assert ga(M=384, N=4096, Kp=65536, ldy=4096) == B.WORKSPACE_TOO_SMALL
+    assert b"built-in" in B.lib().arcq_last_error()
+
+
 def test_check_perm_argument_errors():
     r = ctypes.c_int(0)
     assert B.lib().arcq_check_perm(None, 16, FAKE, ctypes.byref(r), None) == B.INVALID_ARG
