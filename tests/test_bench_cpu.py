@@ -20,8 +20,32 @@ def test_algorithmic_byte_and_flop_counts():
     assert bench.quantizer_bytes(8192, 28672, 1024) == 8192 * (2 * 28672 + 29696 // 2 + 29696 // 16) == 606601216
     assert abs(bench.gemm_flops(8192, 8192, 29696) - 3.9857e12) < 1e9
     assert bench.gemm_bytes(16, 4096, 14592) == (16 + 4096) * (7296 + 912) + 16 * 4096 * 2
-    for wl, d in bench.MEASURED_TRAFFIC.items():
+
+
+def test_traffic_comes_from_the_committed_counter_summary():
+    sys.path.insert(0, ROOT)
+    import bench
+    traffic = bench.load_traffic()
+    assert os.path.exists(os.path.join(ROOT, bench.TRAFFIC_FILE))
+    assert {"c2_llama8b_q", "c3a_llama8b_up", "c3b_llama8b_down", "c4_qwen32b_mlp", "c5_llama70b_down"} <= set(traffic)
+    for wl, d in traffic.items():
         assert {"arcq_gemm", "arcq_quantize_act"} <= set(d) and all(v > 0 for v in d.values())
+    # the quantizer moves its algorithmic bytes once: the counters must agree with the byte count within a few per cent
+    q = traffic["c5_llama70b_down"]["arcq_quantize_act"]
+    assert 0.95 < q / bench.quantizer_bytes(8192, 28672, 1024) < 1.10
+
+
+def test_verification_sample_touches_every_tile_and_both_ends():
+    sys.path.insert(0, ROOT)
+    import numpy as np
+    import bench
+    rng = np.random.default_rng(0)
+    idx = bench.sample_indices(8192, 256, 48, rng)
+    assert idx[0] == 0 and idx[-1] == 8191 and len(idx) <= 34
+    assert {i // 256 for i in idx} == set(range(32))
+    idx = bench.sample_indices(27648, 256, 96, rng)
+    assert idx[0] == 0 and idx[-1] == 27647 and len(idx) <= 98 and len({i // 256 for i in idx}) >= 96
+    assert bench.sample_indices(16, 256, 48, rng)[0] == 0 and bench.sample_indices(1, 256, 48, rng) == [0]
 
 
 def test_profiles_name_their_commands():
