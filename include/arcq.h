@@ -55,6 +55,7 @@ typedef int arcq_status;
 /* flags of the *_ex entry points (0 = the behaviour of the plain entry points) */
 #define ARCQ_LAYOUT_INTERLEAVED 1u   /* Appendix D "Interleaved Channel Layout" */
 #define ARCQ_SCALE_ROUND_UP     2u   /* block scale never below max/q_max: alpha >= 1 of Section 3.4 */
+#define ARCQ_RMSNORM_EXACT_SUM  4u   /* arcq_rmsnorm_quantize_act_ex only: see there */
 
 /* Library version, major*10000 + minor*100 + patch. */
 int arcq_version(void);
@@ -78,8 +79,10 @@ arcq_status arcq_packed_sizes(int64_t rows, int64_t K, int64_t S,
  *       with the same tensor_scale;
  *   (3) output [Q_X | Q_R], [s_X | s_R] in the K' layout.
  * x       fp16 [M, K], row pitch ldx elements (ldx >= K); x 16-byte aligned, ldx % 8 == 0
- * perm    int32 [K], a permutation of 0..K-1 (not checked; see arcq_check_perm):
- *         reordered position j takes source channel perm[j]; outliers are the LAST S positions
+ * perm    int32 [K], 16-byte aligned, a permutation of 0..K-1 (not checked; see arcq_check_perm):
+ *         reordered position j takes source channel perm[j]; outliers are the LAST S positions.
+ *         With entries outside 0..K-1 the output is unspecified; no global memory outside the
+ *         arguments is touched.
  * codes   out, uint8 [M, (K+S)/2], 8-byte aligned;  scales out, uint8 [M, (K+S)/16]
  */
 arcq_status arcq_quantize_act(const void* x, int64_t M, int64_t K, int64_t ldx,
@@ -90,10 +93,11 @@ arcq_status arcq_quantize_act(const void* x, int64_t M, int64_t K, int64_t ldx,
  * The same quantizer with RMSNorm in front, as one kernel (Section 3.3: the fused quantization
  * kernel integrates channel reordering, RMSNorm, primary and residual quantization).  The paper
  * gives no formula; this is y = x / sqrt(mean(x^2) + eps) * gamma with the roundings of the
- * reference layer: mean of squares summed in fp64 and rounded to fp32, rstd = 1/sqrt(ms + eps)
- * in fp32 (correctly rounded), x * rstd rounded to fp16, times gamma rounded to fp16; the result
- * equals arcq_quantize_act applied to that fp16 tensor.  tensor_scale refers to the NORMALISED
- * activations.
+ * reference layer: the mean of squares is defined with an EXACT sum of the squares (no summation order
+ * enters the result), rounded once to fp64, divided by K in fp64 and rounded to fp32; rstd =
+ * 1/sqrt(ms + eps) in fp32 (correctly rounded square root and division); x * rstd is rounded to fp32 and
+ * then to fp16; times gamma, rounded once to fp16.  The result equals arcq_quantize_act applied to that
+ * fp16 tensor.  tensor_scale refers to the NORMALISED activations.
  * gamma  fp16 [K], indexed by SOURCE channel (before the permutation), 16-byte aligned
  * eps    finite, >= 0
  */
@@ -129,6 +133,10 @@ arcq_status arcq_pack_weight(const void* w, int64_t N, int64_t K, int64_t ldw,
  *   not below amax / (6 * tensor_scale) instead of the nearest one, for primary and residual blocks, so no
  *   element saturates at 6; it still saturates at 448, and a nonzero quotient below the smallest subnormal
  *   2^-9 gets 2^-9 rather than 0.
+ * ARCQ_RMSNORM_EXACT_SUM (arcq_rmsnorm_quantize_act_ex only; elsewhere ARCQ_INVALID_ARG): the kernel normally sums
+ *   the squares of a row in fp64 and falls back to an exact integer sum for the rare row whose mean it cannot
+ *   round with certainty; this bit sends EVERY row through the integer sum.  The output is identical by
+ *   construction (that is what the bit lets a caller verify); the call is slower.
  */
 arcq_status arcq_quantize_act_ex(const void* x, int64_t M, int64_t K, int64_t ldx,
                                  const int32_t* perm, int64_t S, float tensor_scale, uint32_t flags,
@@ -192,31 +200,6 @@ arcq_status arcq_gemm_noalloc(const uint8_t* a_codes, const uint8_t* a_scales, f
  */
 arcq_status arcq_check_perm(const int32_t* perm, int64_t K, uint8_t* flags,
                             int* result_host, void* stream);
-
-/*
- * Diagnostic for measurements (no part of the method): enqueues a kernel in which 4096 waves (four per
- * SIMD on 256 CUs) each issue 4 * iters fp16 32x32x16 matrix instructions on register operands, the
- * instruction arcq_gemm is built on, with no memory traffic in the loop.  Timing the launch gives the
- * matrix rate this machine sustains, the ceiling to read arcq_gemm's roofline fraction against.
- * iters   1 .. 2^20
- * sink    device, ARCQ_PROBE_SINK_FLOATS floats, written (keeps the loop alive), 4-byte aligned
- * flop_host  host pointer: receives the floating-point operations of one launch
- */
-#define ARCQ_PROBE_SINK_FLOATS 262144
-arcq_status arcq_probe_mfma_f16(int iters, float* sink, double* flop_host, void* stream);
-/* The same for the instruction arcq_mx_gemm is built on: 4 * iters scaled FP4 32x32x64 matrix instructions
- * per wave (both operands E2M1, unit block scales); same arguments, same sink size. */
-arcq_status arcq_probe_mfma_fp4(int iters, float* sink, double* flop_host, void* stream);
-
-/*
- * Comparison kernel for measurements (no part of the method): the unquantized linear layer y = x w^T on bf16
- * operands, written on the same tiled skeleton as arcq_mx_gemm (operand rows travel global -> LDS in 128-byte
- * units, v_mfma_f32_32x32x16_bf16, fp32 accumulation), the 16-bit baseline the quantized path is timed against.
- * x  device, bf16 [M, K] row-major, pitch K, 16-byte aligned     w  device, bf16 [N, K] row-major, 16-byte aligned
- * y  device, fp16 [M, N], pitch ldy >= N                         K % 32 == 0, operands below 4 GiB each
- */
-arcq_status arcq_ref_gemm_bf16(const void* x, const void* w, int64_t M, int64_t N, int64_t K, void* y, int64_t ldy,
-                               void* stream);
 
 /*
  * Offline calibration (Section 3.2 "Adaptive Outlier Identification"), two calls.

@@ -1,4 +1,4 @@
-"""Thin ctypes binding of libarcq.so: same names as include/arcq.h, argument marshalling only.
+"""Thin ctypes binding of libarcq.so: same names as include/arcq.h and include/arcq_bench.h, argument marshalling only.
 
 PyTorch supplies device memory and the stream; every step of the path runs in the HIP
 kernels.  There is no fallback: if the library is not built, or a call fails, an exception
@@ -14,10 +14,10 @@ LIB_PATH = os.environ.get("ARCQ_LIBRARY") or os.path.join(_HERE, "libarcq.so")  
 
 OK, INVALID_ARG, BAD_SHAPE, BAD_ALIGN, HIP_ERROR, WORKSPACE_TOO_SMALL = range(6)
 DTYPE_F16, DTYPE_F32 = 0, 1
-LAYOUT_INTERLEAVED, SCALE_ROUND_UP = 1, 2
+LAYOUT_INTERLEAVED, SCALE_ROUND_UP, RMSNORM_EXACT_SUM = 1, 2, 4
 MAX_K = 65536
 
-# every symbol include/arcq.h declares: name -> (restype, argtypes)
+# every symbol include/arcq.h and include/arcq_bench.h declare: name -> (restype, argtypes)
 _i64, _f32, _vp, _sz, _u32 = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint32
 SIGNATURES = {
     "arcq_version": (ctypes.c_int, []),

@@ -27,6 +27,28 @@ arcq_status check_launch(const char* what) {
     return ARCQ_OK;
 }
 
+arcq_status raise_lds_limit(const void* kernel, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipGetDevice: %s", hipGetErrorString(e));
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return ARCQ_OK;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+    if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", kMaxLdsBytes, hipGetErrorString(e));
+    if (dev < 64) done.fetch_or(bit, std::memory_order_release);      // devices past 63 set it on every launch
+    return ARCQ_OK;
+}
+
+int num_cu() {
+    static std::atomic<int> cached[64];
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (dev >= 0 && dev < 64 && (n = cached[dev].load(std::memory_order_relaxed)) > 0) return n;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    if (dev >= 0 && dev < 64) cached[dev].store(n, std::memory_order_relaxed);
+    return n;
+}
+
 namespace {
 
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -37,8 +59,8 @@ arcq_status check_scale(float s, const char* name) {
     return ARCQ_OK;
 }
 
-arcq_status check_flags(uint32_t flags, const char* who) {
-    if (flags & ~(uint32_t)(ARCQ_LAYOUT_INTERLEAVED | ARCQ_SCALE_ROUND_UP))
+arcq_status check_flags(uint32_t flags, const char* who, uint32_t also_allowed = 0) {
+    if (flags & ~(uint32_t)(ARCQ_LAYOUT_INTERLEAVED | ARCQ_SCALE_ROUND_UP | also_allowed))
         return fail(ARCQ_INVALID_ARG, "%s: unknown bits in flags = 0x%x", who, flags);
     return ARCQ_OK;
 }
@@ -57,7 +79,7 @@ arcq_status quantize_entry(int mode, const char* who, const void* x, int64_t row
                            uint32_t flags = 0) {
     clear_error();
     if (arcq_status st = check_KS(K, S)) return st;
-    if (arcq_status st = check_flags(flags, who)) return st;
+    if (arcq_status st = check_flags(flags, who, norm ? ARCQ_RMSNORM_EXACT_SUM : 0u)) return st;
     if (rows < 0 || rows > 0x7FFFFFFF) return fail(ARCQ_BAD_SHAPE, "%s: rows = %lld out of range", who, (long long)rows);
     if (ldx < K) return fail(ARCQ_BAD_SHAPE, "%s: leading dimension %lld < K = %lld", who, (long long)ldx, (long long)K);
     if (arcq_status st = check_scale(s_T, "tensor_scale")) return st;
@@ -68,7 +90,7 @@ arcq_status quantize_entry(int mode, const char* who, const void* x, int64_t row
     if (!aligned(x, 16) || (ldx % 8) != 0)
         return fail(ARCQ_BAD_ALIGN, "%s: input must be 16-byte aligned with a leading dimension that is a multiple of 8", who);
     if (!aligned(codes, 8)) return fail(ARCQ_BAD_ALIGN, "%s: codes must be 8-byte aligned", who);
-    if (!aligned(perm, 4)) return fail(ARCQ_BAD_ALIGN, "%s: perm must be 4-byte aligned", who);
+    if (!aligned(perm, 16)) return fail(ARCQ_BAD_ALIGN, "%s: perm must be 16-byte aligned", who);
     return launch_quantize(mode, x, rows, K, ldx, perm, S, s_T, codes, scales, norm ? gamma : nullptr, eps, flags,
                            static_cast<hipStream_t>(stream));
 }

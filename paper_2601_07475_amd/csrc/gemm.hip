@@ -13,6 +13,7 @@
 // consecutive k of row (lane % 32); lanes 0-31 and 32-63 supply different octets.  A and W use
 // the same lane -> k mapping, so any assignment of octets to lanes sums over all of k.
 #include "internal.h"
+#include "gemm_decode.h"
 #include "gemm_epilogue.h"
 #include "lds_dma.h"
 
@@ -20,52 +21,11 @@
 
 #include <algorithm>
 #include <atomic>
-#include <cstdlib>
 #include <type_traits>
 
 namespace arcq {
 
 namespace {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-// Both halves of a packed fp16 pair set to (E4M3 value of byte b) * 2^-8: (b << 7) read as fp16
-// has the E4M3 exponent and mantissa fields in place with an exponent bias of 15 instead of 7,
-// and the subnormal ranges of the two formats line up.  b <= 0x7E.
-__device__ __forceinline__ half2v scale_pair(uint32_t b) {
-    return __builtin_bit_cast(half2v, b * 0x00800080u);
-}
-
-// Eight E2M1 codes (element i in bits 4i..4i+3) times one block scale -> 8 fp16, exact.
-// v_cvt_scalef32_pk_f16_fp4 turns one byte into two fp16 (low nibble first) times a power of
-// two; 2^8 undoes the 2^-8 of scale_pair.  code * 256 <= 1536 and the product <= 2688 fit fp16.
-__device__ __forceinline__ half8 decode8(uint32_t c, half2v sc) {
-    half2v p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 0) * sc;
-    half2v p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 1) * sc;
-    half2v p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 2) * sc;
-    half2v p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 3) * sc;
-    half8 out = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
-    return out;
-}
-
-// The same with the scale taken from one half of a register that holds the fp16 scales of two blocks:
-// a byte permute spreads two scale bytes (bits 0-7 and 8-15 of s) to bits 0-7 and 16-23, one shift puts
-// both in place, and the packed multiplies broadcast the half they need through their operand-select
-// modifiers.  Two vector instructions per two blocks (four k-steps) instead of two per k-step.
-// `sel` picks the two bytes: 0x0C010C00 takes bytes 0 and 1 of s, 0x0C030C02 bytes 2 and 3.
-__device__ __forceinline__ uint32_t scale_halves(uint32_t s, uint32_t sel) {
-    return __builtin_amdgcn_perm(0u, s, sel) << 7;
-}
-__device__ __forceinline__ half8 decode8_half(uint32_t c, uint32_t halves, int hi) {
-    const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)(hi ? halves >> 16 : halves));
-    const half2v sc = {s, s};
-    half2v p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 0) * sc;
-    half2v p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 1) * sc;
-    half2v p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 2) * sc;
-    half2v p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(c, 256.0f, 3) * sc;
-    half8 out = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
-    return out;
-}
 
 // Accumulates blocks [b_begin, b_end) straight from global memory (no staging): used for the
 // K' tail of the staged kernel and as the whole loop of the fallback kernel.  One iteration
@@ -695,9 +655,8 @@ arcq_status launch_staged(const uint8_t* a_codes, const uint8_t* a_scales, const
     if (splits > 1) {
         // fp32 partial results [splits, M, N] in the workspace, then one pass that adds them
         auto kern = gemm_staged_kernel<WM, WN, GM, GN, float>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
+        static std::atomic<uint64_t> lds_raised{0};
+        if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
         const int64_t stride = (int64_t)M * N;
         hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales,
                            w_codes, w_scales, M, N, nbk, 1.0f, partial, (int64_t)N, tiles_m, tiles_n, splits, stride);
@@ -706,9 +665,8 @@ arcq_status launch_staged(const uint8_t* a_codes, const uint8_t* a_scales, const
                                     ldy, stream);
     }
     auto kern = gemm_staged_kernel<WM, WN, GM, GN, OutT>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-    if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
+    static std::atomic<uint64_t> lds_raised{0};
+    if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales, w_codes,
                        w_scales, M, N, nbk, alpha, y, ldy, tiles_m, tiles_n, 1, (int64_t)0);
     return check_launch("gemm_staged_kernel");
@@ -788,104 +746,142 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    int cbase = 0, first_wave = 0;              // first chunk and first wave of the chunk-at-a-time loop
-    if constexpr (GRP) {
-        const bool grp_ok = (nbk & 7) == 0 &&
-                            ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 7) == 0;
-        const int ngroup = grp_ok ? (nbk >> 5) : 0;        // groups of four whole chunks
-        for (int g = wave; g < ngroup; g += WAVES) {
-            uint4 ca[4][MT], cw[4][NT];
-            uint2 sa2[MT], sw2[NT];
-            const int64_t co = 256 * (int64_t)g + 16 * q, so = 32 * (int64_t)g + 8 * q;
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-#pragma unroll
-                for (int r = 0; r < MT; ++r) ca[m][r] = *reinterpret_cast<const uint4*>(ac[r] + co + 64 * m);
-#pragma unroll
-                for (int t = 0; t < NT; ++t) cw[m][t] = *reinterpret_cast<const uint4*>(wc[t] + co + 64 * m);
-            }
-#pragma unroll
-            for (int r = 0; r < MT; ++r) sa2[r] = *reinterpret_cast<const uint2*>(as[r] + so);
-#pragma unroll
-            for (int t = 0; t < NT; ++t) sw2[t] = *reinterpret_cast<const uint2*>(ws[t] + so);
-            uint32_t ea[2][MT], ew[2][NT];     // [chunk parity][tile]: pairs of chunks (0, 2) / (1, 3)
-#pragma unroll
-            for (int r = 0; r < MT; ++r) transpose_scale_pairs(sa2[r], ea[0][r], ea[1][r]);
-#pragma unroll
-            for (int t = 0; t < NT; ++t) transpose_scale_pairs(sw2[t], ew[0][t], ew[1][t]);
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const uint32_t sel = (m >> 1) ? 0x0C030C02u : 0x0C010C00u;
-                uint32_t ha[MT], hw[NT];       // fp16 scales of the lane's two blocks of chunk m
-#pragma unroll
-                for (int r = 0; r < MT; ++r) ha[r] = scale_halves(ea[m & 1][r], sel);
-#pragma unroll
-                for (int t = 0; t < NT; ++t) hw[t] = scale_halves(ew[m & 1][t], sel);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    half8 fa[MT];
-#pragma unroll
-                    for (int r = 0; r < MT; ++r) {
-                        const uint32_t a32 = k == 0 ? ca[m][r].x : k == 1 ? ca[m][r].y : k == 2 ? ca[m][r].z : ca[m][r].w;
-                        fa[r] = decode8_half(a32, ha[r], k >> 1);
-                    }
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) {
-                        const uint32_t w32 = k == 0 ? cw[m][t].x : k == 1 ? cw[m][t].y : k == 2 ? cw[m][t].z : cw[m][t].w;
-                        const half8 fw = decode8_half(w32, hw[t], k >> 1);
-#pragma unroll
-                        for (int r = 0; r < MT; ++r)
-                            acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[r], fw, acc[r][t], 0, 0, 0);
-                    }
-                }
-            }
-        }
-        cbase = 4 * ngroup;
-        first_wave = ngroup % WAVES;            // the waves that took one group less come first
-    }
-    for (int c0 = cbase + ((wave - first_wave + WAVES) % WAVES) * U; c0 < nchunk; c0 += WAVES * U) {
+    // ---- operand registers of one group of four whole chunks, and of the U chunks of one pass of the chunk loop
+    struct Group {
+        uint4 ca[4][MT], cw[4][NT];
+        uint2 sa2[MT], sw2[NT];
+    };
+    struct Chunks {
         uint4 ca[U][MT], cw[U][NT];
         uint32_t sa[U][MT], sw[U][NT];
+    };
+    // Every load of a group is issued before any of it is used, the scale bytes (used first) first: loads retire
+    // in issue order, so chunk m is decoded as soon as it has landed while the later chunks are still in flight.
+    // (Left to itself the compiler sinks the loads of the later chunks behind the decode of the earlier ones to
+    // save registers, which turns one trip to memory into three; the scheduling barriers behind the calls of
+    // these functions keep the loads where they are written.)
+    auto load_group = [&](int g, Group& G) {
+        const int64_t co = 256 * (int64_t)g + 16 * q, so = 32 * (int64_t)g + 8 * q;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int c = c0 + u;
-            // the lane's two blocks 8c + 2q, 8c + 2q + 1 exist (nbk is even) or lie past the end of the
-            // row: then the lane reads the start of its row instead and both operands count as zero
-            // (codes and scale bytes, so that no stray scale pattern meets a zero)
-            const bool ok = 8 * c + 2 * q < nbk;
-            const int64_t co = ok ? 64 * (int64_t)c + 16 * q : 0, so = ok ? 8 * (int64_t)c + 2 * q : 0;
+        for (int r = 0; r < MT; ++r) G.sa2[r] = *reinterpret_cast<const uint2*>(as[r] + so);
 #pragma unroll
-            for (int r = 0; r < MT; ++r) {
-                ca[u][r] = *reinterpret_cast<const uint4*>(ac[r] + co);
-                sa[u][r] = *reinterpret_cast<const uint16_t*>(as[r] + so);
-                if (!ok) { ca[u][r] = make_uint4(0, 0, 0, 0); sa[u][r] = 0; }
-            }
+        for (int t = 0; t < NT; ++t) G.sw2[t] = *reinterpret_cast<const uint2*>(ws[t] + so);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                cw[u][t] = *reinterpret_cast<const uint4*>(wc[t] + co);
-                sw[u][t] = *reinterpret_cast<const uint16_t*>(ws[t] + so);
-                if (!ok) { cw[u][t] = make_uint4(0, 0, 0, 0); sw[u][t] = 0; }
-            }
+        for (int m = 0; m < 4; ++m) {
+#pragma unroll
+            for (int r = 0; r < MT; ++r) G.ca[m][r] = *reinterpret_cast<const uint4*>(ac[r] + co + 64 * m);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) G.cw[m][t] = *reinterpret_cast<const uint4*>(wc[t] + co + 64 * m);
         }
+    };
+    auto compute_group = [&](const Group& G) {
+        uint32_t ea[2][MT], ew[2][NT];     // [chunk parity][tile]: pairs of chunks (0, 2) / (1, 3)
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int r = 0; r < MT; ++r) transpose_scale_pairs(G.sa2[r], ea[0][r], ea[1][r]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) transpose_scale_pairs(G.sw2[t], ew[0][t], ew[1][t]);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const uint32_t sel = (m >> 1) ? 0x0C030C02u : 0x0C010C00u;
+            uint32_t ha[MT], hw[NT];       // fp16 scales of the lane's two blocks of chunk m
+#pragma unroll
+            for (int r = 0; r < MT; ++r) ha[r] = scale_halves(ea[m & 1][r], sel);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) hw[t] = scale_halves(ew[m & 1][t], sel);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 half8 fa[MT];
 #pragma unroll
                 for (int r = 0; r < MT; ++r) {
-                    const uint32_t a32 = k == 0 ? ca[u][r].x : k == 1 ? ca[u][r].y : k == 2 ? ca[u][r].z : ca[u][r].w;
-                    fa[r] = decode8(a32, scale_pair(k < 2 ? (sa[u][r] & 0xFFu) : (sa[u][r] >> 8)));
+                    const uint32_t a32 = k == 0 ? G.ca[m][r].x : k == 1 ? G.ca[m][r].y : k == 2 ? G.ca[m][r].z : G.ca[m][r].w;
+                    fa[r] = decode8_half(a32, ha[r], k >> 1);
                 }
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    const uint32_t w32 = k == 0 ? cw[u][t].x : k == 1 ? cw[u][t].y : k == 2 ? cw[u][t].z : cw[u][t].w;
-                    const half8 fw = decode8(w32, scale_pair(k < 2 ? (sw[u][t] & 0xFFu) : (sw[u][t] >> 8)));
+                    const uint32_t w32 = k == 0 ? G.cw[m][t].x : k == 1 ? G.cw[m][t].y : k == 2 ? G.cw[m][t].z : G.cw[m][t].w;
+                    const half8 fw = decode8_half(w32, hw[t], k >> 1);
 #pragma unroll
                     for (int r = 0; r < MT; ++r)
                         acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[r], fw, acc[r][t], 0, 0, 0);
                 }
             }
+        }
+    };
+    // the lane's two blocks 8c + 2q, 8c + 2q + 1 of chunk c exist (nbk is even) or lie past the end of the row: then
+    // the lane reads the start of its row instead and both operands count as zero (codes and scale bytes, so that
+    // no stray scale pattern meets a zero).  The zeroing happens at the use, not at the load: a select behind a
+    // load would make the wave wait for it at once.
+    auto load_chunks = [&](int c0, Chunks& T) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + u;
+            const bool ok = 8 * c + 2 * q < nbk;
+            const int64_t co = ok ? 64 * (int64_t)c + 16 * q : 0, so = ok ? 8 * (int64_t)c + 2 * q : 0;
+#pragma unroll
+            for (int r = 0; r < MT; ++r) {
+                T.ca[u][r] = *reinterpret_cast<const uint4*>(ac[r] + co);
+                T.sa[u][r] = *reinterpret_cast<const uint16_t*>(as[r] + so);
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                T.cw[u][t] = *reinterpret_cast<const uint4*>(wc[t] + co);
+                T.sw[u][t] = *reinterpret_cast<const uint16_t*>(ws[t] + so);
+            }
+        }
+    };
+    auto compute_chunks = [&](int c0, const Chunks& T) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool ok = 8 * (c0 + u) + 2 * q < nbk;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                half8 fa[MT];
+#pragma unroll
+                for (int r = 0; r < MT; ++r) {
+                    const uint32_t a32 = k == 0 ? T.ca[u][r].x : k == 1 ? T.ca[u][r].y : k == 2 ? T.ca[u][r].z : T.ca[u][r].w;
+                    fa[r] = decode8(ok ? a32 : 0u, scale_pair(!ok ? 0u : k < 2 ? (T.sa[u][r] & 0xFFu) : (T.sa[u][r] >> 8)));
+                }
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const uint32_t w32 = k == 0 ? T.cw[u][t].x : k == 1 ? T.cw[u][t].y : k == 2 ? T.cw[u][t].z : T.cw[u][t].w;
+                    const half8 fw = decode8(ok ? w32 : 0u, scale_pair(!ok ? 0u : k < 2 ? (T.sw[u][t] & 0xFFu) : (T.sw[u][t] >> 8)));
+#pragma unroll
+                    for (int r = 0; r < MT; ++r)
+                        acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[r], fw, acc[r][t], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    bool grouped = false;
+    if constexpr (GRP)
+        grouped = (nbk & 7) == 0 && ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 7) == 0;
+    if (grouped) {
+        // Whole chunks in groups of four, dealt round-robin to the waves; the up to three chunks behind the last
+        // group go to the waves that took one group less.  With one group per wave and four tiles (the up-projection
+        // shapes) such a wave asks for its left-over chunk FIRST and decodes it last, so that it costs no trip to
+        // memory of its own (1 us of 12 there); with few tiles per wave and several groups the same change made the
+        // kernel 10 % slower (measured), so those variants load it where they use it.
+        constexpr bool HOIST = MT == 1 && NT == 4;
+        const int ngroup = nbk >> 5;
+        const int tail_c = 4 * ngroup + (wave - ngroup % WAVES + WAVES) % WAVES * U;
+        const bool has_tail = tail_c < nchunk;
+        Chunks tail;
+        if (HOIST && has_tail) load_chunks(tail_c, tail);
+        for (int g = wave; g < ngroup; g += WAVES) {
+            Group ga;
+            load_group(g, ga);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_group(ga);
+        }
+        if (!HOIST && has_tail) load_chunks(tail_c, tail);
+        if (has_tail) compute_chunks(tail_c, tail);
+    } else {
+        for (int c0 = wave * U; c0 < nchunk; c0 += WAVES * U) {
+            Chunks T;
+            load_chunks(c0, T);
+            compute_chunks(c0, T);
+        }
     }
 #pragma unroll
     for (int r = 0; r < MT; ++r)
@@ -999,15 +995,13 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
         // 128 x 256 tiles with 8 waves of 64 x 64 (two per SIMD): 5 % faster than 4 waves of 64 x 128 on the
         // 2048 x 4096 x 4352 problem; on the large shapes 4 and 8 waves measure the same
         if (t128x256 >= 192) {
-            // whole stages: the variant whose wave pairs split every stage (6 % faster on the 2048 x 4096 x 4352
-            // problem; the environment switch keeps the plain variant reachable for comparisons)
+            // whole stages: the variant whose wave pairs split every stage (6 % faster on the 2048 x 4096 x 4352 problem)
             {
-                if ((nbk & 7) == 0 && nbk >= 16 && !std::getenv("ARCQ_NO_KPAIR")) {
+                if ((nbk & 7) == 0 && nbk >= 16) {
                     using C = StagedCfg<2, 2, 2, 4>;
                     auto kern = gemm_kpair_kernel<OutT>;
-                    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-                    if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
+                    static std::atomic<uint64_t> lds_raised{0};
+                    if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
                     const int tiles_m = (int)((M + 127) / 128), tiles_n = (int)((N + 255) / 256);
                     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(512), C::LDS_BYTES, stream, a_codes, a_scales, w_codes,
                                        w_scales, (int)M, (int)N, nbk, alpha, y, ldy, tiles_m, tiles_n);

@@ -1,10 +1,13 @@
 // Internal declarations shared by the translation units of libarcq (host side only).
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <stddef.h>
 #include <stdint.h>
 
 #include "../../include/arcq.h"
+#include "../../include/arcq_bench.h"
 
 namespace arcq {
 
@@ -14,6 +17,14 @@ void clear_error();
 
 // After a kernel launch: turns a pending HIP launch error into ARCQ_HIP_ERROR.
 arcq_status check_launch(const char* what);
+
+// Kernels with more than 48 KB of dynamic LDS need their limit raised once per device.  `done` is a bit mask
+// over device indices, one static per kernel instantiation; the limit is raised to the whole 160 KB of a
+// compute unit, so one call serves every launch shape of that kernel.
+constexpr int kMaxLdsBytes = 160 * 1024;
+arcq_status raise_lds_limit(const void* kernel, std::atomic<uint64_t>& done);
+// Compute units of the current device (cached per device).
+int num_cu();
 
 // mode 0: activations (residual blocks appended); mode 1: weights (outlier blocks duplicated).
 // gamma != nullptr (mode 0 only): RMSNorm with that weight and eps in front of the quantizer.

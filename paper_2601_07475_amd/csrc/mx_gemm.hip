@@ -368,6 +368,13 @@ __global__ __launch_bounds__(WAVES * 64) void mx_gemm_skinny_kernel(
         for (int g = wave; g < ngroup; g += WAVES) {
             uint4 ca[4][MT], cw[4][NT];
             uint32_t sa[MT], sw[NT];
+            // the scale bytes are needed first (their transpose precedes the first matrix instruction) and loads retire
+            // in issue order: asked for first, they do not make the wave wait for the whole group's codes; the
+            // scheduling barrier keeps every load of the group ahead of its first use
+#pragma unroll
+            for (int r = 0; r < MT; ++r) sa[r] = *reinterpret_cast<const uint32_t*>(as[r] + 16 * (int64_t)g + 4 * q);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) sw[t] = *reinterpret_cast<const uint32_t*>(ws[t] + 16 * (int64_t)g + 4 * q);
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
 #pragma unroll
@@ -375,10 +382,7 @@ __global__ __launch_bounds__(WAVES * 64) void mx_gemm_skinny_kernel(
 #pragma unroll
                 for (int t = 0; t < NT; ++t) cw[m][t] = *reinterpret_cast<const uint4*>(wc[t] + 256 * (int64_t)g + 64 * m);
             }
-#pragma unroll
-            for (int r = 0; r < MT; ++r) sa[r] = *reinterpret_cast<const uint32_t*>(as[r] + 16 * (int64_t)g + 4 * q);
-#pragma unroll
-            for (int t = 0; t < NT; ++t) sw[t] = *reinterpret_cast<const uint32_t*>(ws[t] + 16 * (int64_t)g + 4 * q);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int r = 0; r < MT; ++r) sa[r] = transpose_scale_bytes(sa[r], sel_half, sel_byte);
 #pragma unroll
@@ -474,9 +478,8 @@ arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, co
     if (splits > 1) {
         // fp32 partial results [splits, M, N] in the workspace, then one pass that adds them
         auto kern = mx_gemm_staged_kernel<WM, WN, GM, GN, float, BF16>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
+        static std::atomic<uint64_t> lds_raised{0};
+        if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
         hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales,
                            w_codes, w_scales, M, N, nb, partial, (int64_t)N, tiles_m, tiles_n, splits, (int64_t)M * N);
         if (arcq_status st = check_launch("mx_gemm_staged_kernel (split K)")) return st;
@@ -484,9 +487,8 @@ arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, co
                                     ldy, stream);
     }
     auto kern = mx_gemm_staged_kernel<WM, WN, GM, GN, OutT, BF16>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-    if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%d): %s", C::LDS_BYTES, hipGetErrorString(e));
+    static std::atomic<uint64_t> lds_raised{0};
+    if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales, w_codes,
                        w_scales, M, N, nb, y, ldy, tiles_m, tiles_n, 1, (int64_t)0);
     return check_launch("mx_gemm_staged_kernel");

@@ -297,11 +297,8 @@ template <int BPT, int MODE, bool DB, bool STREAM, bool PAIRS = false>
 arcq_status launch_mx_t(int threads, size_t lds, const void* x, int64_t rows, int64_t K, int64_t ldx,
                         const int32_t* perm, int64_t S, uint8_t* codes, uint8_t* scales, uint32_t flags, hipStream_t stream) {
     auto kern = PAIRS ? mx_quantize_pairs_kernel<MODE, STREAM> : mx_quantize_rows_kernel<BPT, MODE, DB, STREAM>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%zu): %s", lds, hipGetErrorString(e));
-    }
+    static std::atomic<uint64_t> lds_raised{0};
+    if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
     // as many workgroups as the chip holds at once, never more than rows
     static thread_local int cached_threads = 0, cached_per_cu = 0;
     static thread_local size_t cached_lds = 0;
@@ -315,10 +312,7 @@ arcq_status launch_mx_t(int threads, size_t lds, const void* x, int64_t rows, in
         cached_lds = lds;
         cached_per_cu = n;
     }
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        cus = 256;
-    int64_t wgs = (int64_t)cus * cached_per_cu;
+    int64_t wgs = (int64_t)num_cu() * cached_per_cu;
     if (wgs > rows) wgs = rows;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(threads), lds, stream, static_cast<const uint16_t*>(x), ldx,
                        (int)rows, (int)K, (int)S, perm, codes, scales, flags);

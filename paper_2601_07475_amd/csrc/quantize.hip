@@ -18,8 +18,6 @@
 
 #include <hip/hip_fp16.h>
 
-#include <cstdlib>
-
 namespace arcq {
 
 namespace {
@@ -164,7 +162,8 @@ void quantize_rows_kernel(
     }
     if (GAMMA_REGS) {
         auto g16 = [&](uint32_t byte_off) -> uint32_t {
-            return NORM == 1 ? *reinterpret_cast<const uint16_t*>(lds_gamma + byte_off) : gamma[byte_off >> 1];
+            // an index from an unchecked perm may exceed K: keep the global read inside gamma
+            return NORM == 1 ? *reinterpret_cast<const uint16_t*>(lds_gamma + byte_off) : gamma[min(byte_off >> 1, (uint32_t)K - 1u)];
         };
 #pragma unroll
         for (int j = 0; j < BPT; ++j)
@@ -378,29 +377,13 @@ void quantize_rows_kernel(
     }
 }
 
-int g_num_cu = 0;
-
-int num_cu() {
-    if (g_num_cu == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            n = 256;
-        g_num_cu = n;
-    }
-    return g_num_cu;
-}
-
 template <int BPT, int MODE, bool DB, bool STREAM, int NORM>
 arcq_status launch_t(int threads, int grid /* workgroups per CU, an estimate */, size_t lds, const void* x, int64_t rows, int64_t K,
                      int64_t ldx, const int32_t* perm, int64_t S, float s_T, float ginv,
                      uint8_t* codes, uint8_t* scales, const void* gamma, float eps, uint32_t flags, hipStream_t stream) {
     auto kern = quantize_rows_kernel<BPT, MODE, DB, STREAM, NORM>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return fail(ARCQ_HIP_ERROR, "hipFuncSetAttribute(LDS=%zu): %s", lds, hipGetErrorString(e));
-    }
+    static std::atomic<uint64_t> lds_raised{0};
+    if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
     // One workgroup per row slot the chip can hold at once (registers and LDS decide; asked of the runtime
     // once per kernel variant and workgroup shape), never more than rows: every workgroup then loops over
     // its rows with the next row's copy in flight, and none waits for a slot.
@@ -419,10 +402,10 @@ arcq_status launch_t(int threads, int grid /* workgroups per CU, an estimate */,
     grid = cached_per_cu;
     int64_t wgs = (int64_t)num_cu() * grid;
     if (wgs > rows) wgs = rows;
-    // relative half-width of the fast path's bracket, see the kernel; the environment switch sends every
-    // row through the exact integer sum instead (for tests of that path; results are identical)
+    // relative half-width of the fast path's bracket, see the kernel; ARCQ_RMSNORM_EXACT_SUM sends every
+    // row through the exact integer sum instead (results are identical)
     const double delta = (double)(K + 260) * 0x1p-52;
-    const int force_exact = NORM != 0 && std::getenv("ARCQ_RMSNORM_EXACT_SUM") != nullptr;
+    const int force_exact = NORM != 0 && (flags & ARCQ_RMSNORM_EXACT_SUM) != 0;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(threads), lds, stream,
                        static_cast<const uint16_t*>(x), ldx, (int)rows, (int)K, (int)S, perm, s_T,
                        ginv, codes, scales, static_cast<const uint16_t*>(gamma), eps, delta, 1.0 / (double)K, force_exact, flags);

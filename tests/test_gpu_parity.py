@@ -101,11 +101,19 @@ def norm_case(M, K, S, seed):
     return X, gamma, wk.calibrate_perm(Yn), wk.tensor_scale(Yn)
 
 
-def gpu_norm_quantize(X, gamma, eps, perm, S, sT):
+def norm_quantize_call(stats_path):
+    """arcq_rmsnorm_quantize_act, or its _ex form with the flag that forces the integer sum."""
+    if stats_path == "integer_sum":
+        return lambda x, g, eps, p, S, t, **kw: B.arcq_rmsnorm_quantize_act_ex(x, g, eps, p, S, t, B.RMSNORM_EXACT_SUM, **kw)
+    return B.arcq_rmsnorm_quantize_act
+
+
+def gpu_norm_quantize(X, gamma, eps, perm, S, sT, stats_path="bracketed_sum"):
     g = dev(gamma)
+    call = norm_quantize_call(stats_path)
 
     def fn(x, p, S_, t, codes, scales):
-        return B.arcq_rmsnorm_quantize_act(x, g, eps, p, S_, t, codes=codes, scales=scales)
+        return call(x, g, eps, p, S_, t, codes=codes, scales=scales)
     return gpu_quantize(fn, X, perm, S, sT)
 
 
@@ -116,14 +124,10 @@ NORM_SHAPES = [  # blocks per lane 1..4, one and two row buffers, lane tails, S 
 
 
 @pytest.fixture(params=["bracketed_sum", "integer_sum"])
-def stats_path(request, monkeypatch):
+def stats_path(request):
     """The kernel sums the squares in fp64 and falls back to an exact integer sum for the rare row
-    whose mean it cannot round with certainty; the environment switch sends every row through the
+    whose mean it cannot round with certainty; the ARCQ_RMSNORM_EXACT_SUM flag sends every row through the
     integer sum, so both paths are held to the same oracle."""
-    if request.param == "integer_sum":
-        monkeypatch.setenv("ARCQ_RMSNORM_EXACT_SUM", "1")
-    else:
-        monkeypatch.delenv("ARCQ_RMSNORM_EXACT_SUM", raising=False)
     return request.param
 
 
@@ -133,7 +137,7 @@ def test_rmsnorm_quantize_act_bit_exact(M, K, S, stats_path):
     X, gamma, perm, sT = norm_case(M, K, S, seed=300 + K % 89)
     for eps in (1e-5, 0.0):
         want_c, want_s = A.rmsnorm_quantize_act(X, gamma, eps, perm, S, sT)
-        got_c, got_s = gpu_norm_quantize(X, gamma, eps, perm, S, sT)
+        got_c, got_s = gpu_norm_quantize(X, gamma, eps, perm, S, sT, stats_path)
         assert_same_bytes(got_s, want_s, f"scales eps={eps}")
         assert_same_bytes(got_c, want_c, f"codes eps={eps}")
 
@@ -166,7 +170,7 @@ def test_rmsnorm_quantize_edge_rows_and_strided_input(stats_path):
         want_c, want_s = A.quantize_act(Yn, perm, S, sT)
         wide = torch.full((12, K + 40), 3.0, dtype=torch.float16, device="cuda")
         wide[:, :K] = dev(X)
-        cc, ss = B.arcq_rmsnorm_quantize_act(wide[:, :K], dev(gamma), eps, dev(perm), S, sT)
+        cc, ss = norm_quantize_call(stats_path)(wide[:, :K], dev(gamma), eps, dev(perm), S, sT)
         assert_same_bytes(ss.cpu().numpy(), want_s, f"scales eps={eps}")
         assert_same_bytes(cc.cpu().numpy(), want_c, f"codes eps={eps}")
 
@@ -176,7 +180,7 @@ def test_rmsnorm_quantize_full_size_qproj(stats_path):
     say(f"rmsnorm_quantize_act full size 2048 x 4096 {stats_path}")
     X, gamma, perm, sT = norm_case(2048, 4096, 256, seed=41)
     want_c, want_s = A.rmsnorm_quantize_act(X, gamma, 1e-5, perm, 256, sT)
-    got_c, got_s = gpu_norm_quantize(X, gamma, 1e-5, perm, 256, sT)
+    got_c, got_s = gpu_norm_quantize(X, gamma, 1e-5, perm, 256, sT, stats_path)
     assert_same_bytes(got_s, want_s, "scales")
     assert_same_bytes(got_c, want_c, "codes")
 

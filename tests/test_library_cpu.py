@@ -9,13 +9,13 @@ import pytest
 from paper_2601_07475_amd import binding as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "arcq.h")
+HEADERS = [os.path.join(ROOT, "include", h) for h in ("arcq.h", "arcq_bench.h")]
 
 pytestmark = pytest.mark.skipif(not os.path.exists(B.LIB_PATH), reason="libarcq.so not built")
 
 
 def declared_symbols():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(arcq_[a-z0-9_]+)\s*\(", text)))
 
@@ -65,6 +65,8 @@ def test_quantizer_argument_errors(fn):
     assert q(fn, ld=516) == B.BAD_ALIGN
     assert q(fn, codes=ODD) == B.BAD_ALIGN
     assert b"aligned" in B.lib().arcq_last_error()
+    assert q(fn, perm=ODD) == B.BAD_ALIGN and q(fn, perm=ctypes.c_void_p(0x10008)) == B.BAD_ALIGN    # read as 16-byte vectors
+    assert b"perm" in B.lib().arcq_last_error()
     assert q(fn, rows=0, x=None, perm=None, codes=None, scales=None) == B.OK      # empty input: nothing to do
     assert B.lib().arcq_last_error() == b""
 
@@ -193,6 +195,10 @@ def test_variant_entry_points_argument_errors():
             assert fn(None, 0, 512, 512, None, 32, 1.0, flags, None, None, None) == B.OK      # nothing to do
     nq = L.arcq_rmsnorm_quantize_act_ex
     assert nq(FAKE, 4, 512, 512, FAKE, 1e-5, FAKE, 32, 1.0, 8, FAKE, FAKE, None) == B.INVALID_ARG
+    # the exact-sum bit belongs to the RMSNorm call alone
+    assert nq(None, 0, 512, 512, None, 1e-5, None, 32, 1.0, 4 | 3, None, None, None) == B.OK
+    assert L.arcq_quantize_act_ex(None, 0, 512, 512, None, 32, 1.0, 4, None, None, None) == B.INVALID_ARG
+    assert B.RMSNORM_EXACT_SUM == 4
     assert nq(FAKE, 4, 512, 512, None, 1e-5, FAKE, 32, 1.0, 1, FAKE, FAKE, None) == B.INVALID_ARG   # gamma
     assert nq(None, 0, 512, 512, None, 1e-5, None, 32, 1.0, 3, None, None, None) == B.OK
     for fn in (L.arcq_mx_quantize_act_ex, L.arcq_mx_pack_weight_ex):

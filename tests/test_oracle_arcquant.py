@@ -169,8 +169,15 @@ def test_calibration_permutation_convention():
     assert np.array_equal(X[:, perm][:, inv], X)
     T = np.zeros((2, 32), dtype=np.float16)
     T[0] = [3, 1, 3, 2] * 8                                     # deliberate ties
-    p = wk.calibrate_perm(T)
-    assert p.tolist() == [i for v in (1, 2, 3) for i in range(32) if T[0, i] == v]
+    want = [i for v in (1, 2, 3) for i in range(32) if T[0, i] == v]
+    assert wk.calibrate_perm(T).tolist() == want                # the harness's stand-in
+    from oracle import calibration as CAL                        # and the oracle's calibration step (Section 3.2)
+    sel = CAL.select_outliers(CAL.absmax_update(np.zeros(32, np.float32), T))
+    assert sel["perm"].tolist() == want
+    full = CAL.select_outliers(CAL.absmax_update(np.zeros(K, np.float32), X))
+    assert np.array_equal(full["perm"], perm)
+    cm = np.abs(X).max(axis=0).astype(np.float32)
+    assert cm[full["perm"][K - full["S_raw"]:]].min() > full["tau"] >= cm[full["perm"][:K - full["S_raw"]]].max()
     # the quantizer gathers: reordered position j reads source channel perm[j]
     Xq = np.zeros((1, 32), dtype=np.float16)
     Xq[0, 5] = 6.0
