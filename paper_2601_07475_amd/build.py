@@ -13,7 +13,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libarcq.so")
-SOURCES = ["api.hip", "quantize.hip", "gemm.hip", "check_perm.hip", "calibrate.hip", "mx_quantize.hip", "mx_gemm.hip", "probe.hip"]
+SOURCES = ["api.hip", "quantize.hip", "gemm.hip", "gemm_ksplit.hip", "check_perm.hip", "calibrate.hip", "mx_quantize.hip", "mx_gemm.hip", "probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -930,6 +930,7 @@ static bool skinny_shape(int64_t M, int64_t N, int64_t Kp) {
 int split_k(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nbk = Kp >> 4;
     if (skinny_shape(M, N, Kp) || (nbk & 3) != 0 || nbk < 8) return 1;
+    if (gemm_ksplit_variant(M, N, Kp) != 0) return 1;      // the k split happens inside the workgroups
     if (((M + 255) / 256) * ((N + 255) / 256) >= 256 || ((M + 127) / 128) * ((N + 255) / 256) >= 192) return 1;
     const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
     if (tiles > 128) return 1;
@@ -986,6 +987,10 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
     const bool offsets_fit = (uint64_t)M * (uint64_t)nbk * 8 < 0xFFFF0000ull && (uint64_t)N * (uint64_t)nbk * 8 < 0xFFFF0000ull;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
                            ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 3) == 0;
+    if (aligned16)
+        if (const int variant = gemm_ksplit_variant(M, N, Kp))
+            return launch_gemm_ksplit(variant, a_codes, a_scales, w_codes, w_scales, M, N, Kp, alpha, y,
+                                      std::is_same<OutT, _Float16>::value ? ARCQ_DTYPE_F16 : ARCQ_DTYPE_F32, ldy, stream);
     if ((nbk & 3) == 0 && nbk >= 8 && offsets_fit && aligned16) {
         // big tiles when they still give every CU work; otherwise smaller ones
         const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);

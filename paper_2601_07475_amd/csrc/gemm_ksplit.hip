@@ -1,0 +1,341 @@
+// Tiled W4A4 GEMM for problems with few output tiles (a few hundred activation rows; Section 3.2 eq. (2)): the waves
+// of a workgroup split every stage along k INSIDE the compute unit, so a small output tile still keeps all four
+// SIMDs busy and the chip gets one tile per compute unit without a round trip of fp32 partial results through
+// HBM and a second launch (which is what splitting K' across workgroups costs).
+//
+// Workgroup tile BM x BN = 32 WM GM x 32 WN GN, computed by GM x GN x KS waves: wave (wq, kh) accumulates the
+// WM x WN fragments of sub-tile wq over the k-quarter kh of every stage.  A stage is 64 KS k (256 for KS = 4): per
+// row 32 KS code bytes (2 KS pieces of 16 bytes) and 4 KS scale bytes, kept packed in LDS and decoded in registers
+// (gemm_decode.h); wave kh reads pieces 2 kh and 2 kh + 1 of a row (lanes 0-31 the first, lanes 32-63 the second:
+// four k-steps, as in the wave-pair kernel of gemm.hip, whose schedule this kernel shares) and the scale word at
+// byte 4 kh.  Stages travel global -> LDS with global_load_lds through a ring of three buffers.  The 16-byte
+// pieces of a row are XOR-swizzled so that 16 consecutive rows fall on 16 different bank groups (rows are 128
+// bytes apart for KS = 4: swizzle (row >> 1) & 7; 64 bytes for KS = 2: (row >> 2) & 3).
+// At the end the KS partial tiles are added through the LDS in KS - 1 rounds; fragment f of a sub-tile is owned
+// (finished and stored) by wave kh = f % KS.
+#include "internal.h"
+#include "gemm_decode.h"
+#include "gemm_epilogue.h"
+#include "lds_dma.h"
+
+#include <type_traits>
+
+namespace arcq {
+
+namespace {
+
+template <int WM, int WN, int GM, int GN, int KS>
+struct KsplitCfg {
+    static_assert(KS == 2 || KS == 4, "k halves or quarters");
+    static_assert((WM * WN) % KS == 0, "every wave owns the same number of fragments");
+    static constexpr int BM = 32 * WM * GM, BN = 32 * WN * GN;
+    static constexpr int NWAVE = GM * GN * KS, NT = 64 * NWAVE;
+    static constexpr int ROWB = 32 * KS;            // code bytes of a row per stage
+    static constexpr int PPR = 2 * KS;              // 16-byte pieces of a row per stage
+    static constexpr int SROWB = 4 * KS;            // scale bytes of a row per stage
+    // copy instructions per thread and stage (a copy always involves the whole workgroup; surplus lanes re-fetch
+    // the operand's last rows into padding behind its region, so that every wave issues the same number)
+    static constexpr int NA = (BM * PPR + NT - 1) / NT, NW = (BN * PPR + NT - 1) / NT;
+    static constexpr int NAS = (BM * KS + NT - 1) / NT, NWS = (BN * KS + NT - 1) / NT;
+    static constexpr int NDMA = NA + NW + NAS + NWS;
+    static constexpr int A_CODES = 0;
+    static constexpr int W_CODES = NA * NT * 16;
+    static constexpr int A_SCALES = W_CODES + NW * NT * 16;
+    static constexpr int W_SCALES = A_SCALES + NAS * NT * 4;
+    static constexpr int STAGE_BYTES = W_SCALES + NWS * NT * 4;
+    static constexpr int NSTAGE = 3, DIST = 2;
+    static constexpr int OWN = WM * WN / KS;         // fragments a wave finishes and stores
+    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+    static_assert(NWAVE * OWN * 4096 <= LDS_BYTES, "the exchange regions must fit the operand ring");
+    static_assert((NT / PPR) % 16 == 0 && (NT / KS) % 1 == 0, "row swizzle must not depend on the copy index");
+    static_assert((DIST - 1) * NDMA < 64, "the vector-memory counter has 6 bits");
+};
+
+// One 32 x 32 fragment computed with the weights as the row operand: lane holds output row m0 + lane % 32, register
+// e holds column n0 + 8 (e / 4) + 4 (lane / 32) + e % 4.
+template <typename OutT>
+__device__ __forceinline__ void store_fragment(const float16v& a, int m0, int n0, int r, int h, int M, int N, float alpha,
+                                               OutT* __restrict__ y, int64_t ldy, bool vec_ok) {
+    const int m = m0 + r;
+    if (m >= M) return;
+    OutT* yrow = y + (int64_t)m * ldy;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int n = n0 + 8 * g + 4 * h;
+        const float v0 = a[4 * g] * alpha, v1 = a[4 * g + 1] * alpha, v2 = a[4 * g + 2] * alpha, v3 = a[4 * g + 3] * alpha;
+        if (vec_ok && n + 3 < N) {
+            store4(yrow + n, v0, v1, v2, v3);
+        } else {
+            if (n < N) store_out(yrow + n, v0);
+            if (n + 1 < N) store_out(yrow + n + 1, v1);
+            if (n + 2 < N) store_out(yrow + n + 2, v2);
+            if (n + 3 < N) store_out(yrow + n + 3, v3);
+        }
+    }
+}
+
+template <int WM, int WN, int GM, int GN, int KS, typename OutT>
+__global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
+    const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
+    const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N,
+    int nbk, float alpha, OutT* __restrict__ y, int64_t ldy, int tiles_m, int tiles_n) {
+    using C = KsplitCfg<WM, WN, GM, GN, KS>;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+
+    // workgroup -> tile: workgroups are dealt round-robin to the 8 XCDs (each with its own L2); every XCD gets a
+    // contiguous run of the tile sequence, walked in column-major groups of 8 tile rows
+    const int num_tiles = tiles_m * tiles_n;
+    int pid = (int)blockIdx.x;
+    if ((num_tiles & 7) == 0) pid = (pid & 7) * (num_tiles >> 3) + (pid >> 3);
+    constexpr int GROUP = 8;
+    const int group_size = GROUP * tiles_n;
+    const int g = pid / group_size;
+    const int first_m = g * GROUP;
+    const int gm = min(GROUP, tiles_m - first_m);
+    const int in_g = pid - g * group_size;
+    const int tile_m = first_m + in_g % gm;
+    const int tile_n = in_g / gm;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int kh = wave / (GM * GN);                 // k share: k-steps 4 kh .. 4 kh + 3 of every stage
+    const int wq = wave % (GM * GN);
+    const int wg_m0 = tile_m * C::BM, wg_n0 = tile_n * C::BN;
+    const int wrow0 = (wq / GN) * (32 * WM);         // first row of this wave inside the A tile
+    const int wcol0 = (wq % GN) * (32 * WN);         // first row of this wave inside the W tile
+    const int nstage = nbk / (4 * KS);               // stages of 4 KS blocks (the launcher checks divisibility)
+
+    // ---- copies
+    auto swz = [](int row) -> uint32_t { return KS == 4 ? (uint32_t)(row >> 1) & 7u : (uint32_t)(row >> 2) & 3u; };
+    const int crow = tid / C::PPR, srow = tid / KS;  // row of this thread inside a copy of NT / PPR code rows / NT / KS scale rows
+    const uint32_t adj_c = 16u * ((uint32_t)(tid % C::PPR) ^ swz(crow));
+    const uint32_t adj_s = 4u * (uint32_t)(tid % KS);
+    const uint32_t cpitch32 = (uint32_t)nbk * 8u, spitch32 = (uint32_t)nbk;
+    const uint32_t wave_slot = __builtin_amdgcn_readfirstlane((uint32_t)(tid & ~63));
+    const uint32_t lds0 = lds_address(lds);
+    auto issue_one = [&](int d, int stage, int buf) {
+        const uint32_t base = lds0 + buf * C::STAGE_BYTES;
+        const uint32_t oc = (uint32_t)stage * C::ROWB + adj_c;
+        const uint32_t os = (uint32_t)stage * C::SROWB + adj_s;
+        constexpr int NA = C::NA, NW = C::NW, NAS = C::NAS, NT = C::NT;
+        // rows past the edge of the operand re-read its last row (never stored)
+        if (d < NA) {
+            const uint32_t row = (uint32_t)min(wg_m0 + d * (NT / C::PPR) + crow, M - 1);
+            dma16(a_codes, row * cpitch32 + oc, base + C::A_CODES + 16u * (d * NT + wave_slot));
+        } else if (d < NA + NW) {
+            const int p = d - NA;
+            const uint32_t row = (uint32_t)min(wg_n0 + p * (NT / C::PPR) + crow, N - 1);
+            dma16(w_codes, row * cpitch32 + oc, base + C::W_CODES + 16u * (p * NT + wave_slot));
+        } else if (d < NA + NW + NAS) {
+            const int p = d - NA - NW;
+            const uint32_t row = (uint32_t)min(wg_m0 + p * (NT / KS) + srow, M - 1);
+            dma4(a_scales, row * spitch32 + os, base + C::A_SCALES + 4u * (p * NT + wave_slot));
+        } else {
+            const int p = d - NA - NW - NAS;
+            const uint32_t row = (uint32_t)min(wg_n0 + p * (NT / KS) + srow, N - 1);
+            dma4(w_scales, row * spitch32 + os, base + C::W_SCALES + 4u * (p * NT + wave_slot));
+        }
+    };
+
+    // ---- LDS read offsets: this wave's share of a stage is piece 2 kh + h of a row's codes and the scale word at
+    // byte 4 kh; fragment i of a wave is 32 rows further on (the swizzle only depends on lane % 32 because the other
+    // terms are multiples of 32)
+    const uint32_t piece = 16u * ((uint32_t)(2 * kh + h) ^ swz(r));
+    const uint32_t rd_a = C::A_CODES + (wrow0 + r) * C::ROWB + piece, rd_w = C::W_CODES + (wcol0 + r) * C::ROWB + piece;
+    const uint32_t rd_as = C::A_SCALES + (wrow0 + r) * C::SROWB + 4 * kh, rd_ws = C::W_SCALES + (wcol0 + r) * C::SROWB + 4 * kh;
+    const uint32_t scale_sel = h ? 0x0C030C02u : 0x0C010C00u;
+
+    float16v acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    constexpr int G = WM + WN;                 // fragments per k-step
+    constexpr int P = WM * WN;                 // MFMAs per k-step, one per group
+    uint4 ca[WM], cw[WN];
+    uint32_t sa[WM], sw[WN];
+    half8 fa[2][WM], fw[2][WN];
+    auto read_raw = [&](const uint8_t* st) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            ca[i] = *reinterpret_cast<const uint4*>(st + rd_a + i * (32 * C::ROWB));
+            sa[i] = scale_halves(*reinterpret_cast<const uint32_t*>(st + rd_as + i * (32 * C::SROWB)), scale_sel);
+        }
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            cw[j] = *reinterpret_cast<const uint4*>(st + rd_w + j * (32 * C::ROWB));
+            sw[j] = scale_halves(*reinterpret_cast<const uint32_t*>(st + rd_ws + j * (32 * C::SROWB)), scale_sel);
+        }
+    };
+    auto decode_frag = [&](int gidx, int t) {   // fragment gidx of this wave's k-step t (0..3) into slot t & 1
+        const int d = t & 1;
+        if (gidx < WM) {
+            const uint4 c4 = ca[gidx];
+            const uint32_t c = t == 0 ? c4.x : t == 1 ? c4.y : t == 2 ? c4.z : c4.w;
+            fa[d][gidx] = decode8_half(c, sa[gidx], t >> 1);
+        } else {
+            const int j = gidx - WM;
+            const uint4 c4 = cw[j];
+            const uint32_t c = t == 0 ? c4.x : t == 1 ? c4.y : t == 2 ? c4.z : c4.w;
+            fw[d][j] = decode8_half(c, sw[j], t >> 1);
+        }
+    };
+
+    // One stage = four k-steps of this wave.  During step t the fragments of step t + 1 are decoded, one group of
+    // fragments after every MFMA; the raw codes of the next stage are read at the start of step 3 (every fragment of
+    // this stage has been decoded by then) behind the barrier that opens that stage, and step 3 decodes its first
+    // fragments.  The copies of stage s + DIST are issued during steps 0..2, into the buffer of stage s - 1, which
+    // every wave left before the barrier that opened stage s.
+    int buf = 0;
+    auto ring_next = [](int b) { return b == C::NSTAGE - 1 ? 0 : b + 1; };
+    auto run_stage = [&](int s) {
+        const int buf1 = ring_next(buf), buf2 = buf == 0 ? C::NSTAGE - 1 : buf - 1;
+        const int fetch = min(s + C::DIST, nstage - 1);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (t == 3) {
+                wait_vmcnt<(C::DIST - 1) * C::NDMA>();
+                wg_barrier();
+                read_raw(lds + buf1 * C::STAGE_BYTES);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+#pragma unroll
+                for (int gidx = (p * G) / P; gidx < ((p + 1) * G) / P; ++gidx) decode_frag(gidx, (t + 1) & 3);
+                __builtin_amdgcn_sched_barrier(0);
+                const int i = p / WN, j = p % WN;
+                // weights as the row operand: see store_fragment
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[t & 1][j], fa[t & 1][i], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t < 3) {
+#pragma unroll
+                    for (int d = 0; d < C::NDMA; ++d)
+                        if ((d * 3) / C::NDMA == t && (d - (t * C::NDMA + 2) / 3) == p) issue_one(d, fetch, buf2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        buf = buf1;
+    };
+    static_assert((C::NDMA + 2) / 3 <= P, "the copies of a stage are spread over the MFMAs of three k-steps");
+
+#pragma unroll
+    for (int d = 0; d < C::DIST; ++d)
+#pragma unroll
+        for (int q = 0; q < C::NDMA; ++q) issue_one(q, min(d, nstage - 1), d);
+    wait_vmcnt<(C::DIST - 1) * C::NDMA>();
+    wg_barrier();
+    read_raw(lds);
+#pragma unroll
+    for (int gidx = 0; gidx < G; ++gidx) decode_frag(gidx, 0);
+    for (int s = 0; s < nstage; ++s) run_stage(s);
+    wait_vmcnt<0>();                            // no copy may still be in flight when the LDS is released
+
+    // ---- the KS partial tiles of a sub-tile are added through the LDS: in round rho every wave hands the fragments
+    // owned by wave kh + rho (same sub-tile) over and adds what wave kh - rho left for it
+    float* xch = reinterpret_cast<float*>(lds);
+    auto region = [&](int k_share) { return xch + ((k_share * (GM * GN) + wq) * C::OWN) * 1024; };
+#pragma unroll
+    for (int rho = 1; rho < KS; ++rho) {
+        const int dst = (kh + rho) % KS, src = (kh + KS - rho) % KS;
+        wait_lgkmcnt0();                        // this wave's reads of the ring / of the previous round have returned
+        wg_barrier();                           // ring (or the previous round's regions) no longer read by anyone
+#pragma unroll
+        for (int f = 0; f < WM * WN; ++f)
+            if (f % KS == dst) {                // uniform over the wave
+                float* slot = region(kh) + (f / KS) * 1024;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<float4*>(slot + (q * 64 + lane) * 4) =
+                        make_float4(acc[f / WN][f % WN][4 * q], acc[f / WN][f % WN][4 * q + 1], acc[f / WN][f % WN][4 * q + 2],
+                                    acc[f / WN][f % WN][4 * q + 3]);
+            }
+        wait_lgkmcnt0();
+        wg_barrier();
+#pragma unroll
+        for (int f = 0; f < WM * WN; ++f)
+            if (f % KS == kh) {
+                const float* slot = region(src) + (f / KS) * 1024;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = *reinterpret_cast<const float4*>(slot + (q * 64 + lane) * 4);
+                    acc[f / WN][f % WN][4 * q] += v.x;
+                    acc[f / WN][f % WN][4 * q + 1] += v.y;
+                    acc[f / WN][f % WN][4 * q + 2] += v.z;
+                    acc[f / WN][f % WN][4 * q + 3] += v.w;
+                }
+            }
+    }
+    const int m0 = wg_m0 + wrow0, n0 = wg_n0 + wcol0;
+    const bool vec_ok = (ldy & (std::is_same<OutT, _Float16>::value ? 3 : 3)) == 0 &&
+                        (reinterpret_cast<uintptr_t>(y) & (std::is_same<OutT, _Float16>::value ? 7 : 15)) == 0;
+#pragma unroll
+    for (int f = 0; f < WM * WN; ++f)
+        if (f % KS == kh) store_fragment(acc[f / WN][f % WN], m0 + 32 * (f / WN), n0 + 32 * (f % WN), r, h, M, N, alpha, y, ldy, vec_ok);
+}
+
+template <int WM, int WN, int GM, int GN, int KS, typename OutT>
+arcq_status launch_ksplit(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
+                          int M, int N, int nbk, float alpha, OutT* y, int64_t ldy, hipStream_t stream) {
+    using C = KsplitCfg<WM, WN, GM, GN, KS>;
+    auto kern = gemm_ksplit_kernel<WM, WN, GM, GN, KS, OutT>;
+    static std::atomic<uint64_t> lds_raised{0};
+    if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
+    const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales, w_codes, w_scales,
+                       M, N, nbk, alpha, y, ldy, tiles_m, tiles_n);
+    return check_launch("gemm_ksplit_kernel");
+}
+
+template <typename OutT>
+arcq_status launch_ksplit_typed(int variant, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                                const uint8_t* w_scales, int M, int N, int nbk, float alpha, OutT* y, int64_t ldy,
+                                hipStream_t stream) {
+    switch (variant) {
+        case 1: return launch_ksplit<2, 2, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 64 x 64
+        case 2: return launch_ksplit<4, 2, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 128 x 64
+        default: return launch_ksplit<2, 4, 2, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);  // 128 x 128
+    }
+}
+
+}  // namespace
+
+// 0: not served here; 1: 64 x 64 tiles; 2: 128 x 64 tiles; 3: 128 x 128 tiles (k quarters inside the workgroup each)
+int gemm_ksplit_variant(int64_t M, int64_t N, int64_t Kp) {
+    const int64_t nbk = Kp >> 4;
+    if ((nbk & 15) != 0 || nbk < 32) return 0;            // whole stages of 256 k, at least two
+    if ((uint64_t)M * (uint64_t)nbk * 8 >= 0xFFFF0000ull || (uint64_t)N * (uint64_t)nbk * 8 >= 0xFFFF0000ull) return 0;
+#ifdef ARCQ_KSPLIT_FORCE
+    return ARCQ_KSPLIT_FORCE;
+#endif
+    // The smallest tile that still covers the problem with at most one workgroup per compute unit (256), as long as
+    // it occupies more than half of them (measured at 4096 x 4352, 14336 x 4352 and 4096 x 14592 weights, M = 128 ..
+    // 1024: against the 128 x 128 tiles with K' split across workgroups these run 64 x 64 tiles 1.2-1.8x, 128 x 64
+    // tiles 1.1-1.5x and 128 x 128 tiles 1.05-1.2x faster; with fewer tiles the split across workgroups wins, with
+    // more the larger tiles of gemm.hip do).
+    const int64_t m64 = (M + 63) / 64, m128 = (M + 127) / 128, n64 = (N + 63) / 64, n128 = (N + 127) / 128;
+    auto fits = [](int64_t tiles) { return tiles >= 144 && tiles <= 256; };
+    if (fits(m64 * n64)) return 1;
+    if (fits(m128 * n64)) return 2;
+    if (fits(m128 * n128)) return 3;
+    return 0;
+}
+
+arcq_status launch_gemm_ksplit(int variant, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                               const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, float alpha, void* y, int y_dtype,
+                               int64_t ldy, hipStream_t stream) {
+    const int nbk = (int)(Kp >> 4);
+    if (y_dtype == ARCQ_DTYPE_F16)
+        return launch_ksplit_typed<_Float16>(variant, a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha,
+                                             static_cast<_Float16*>(y), ldy, stream);
+    return launch_ksplit_typed<float>(variant, a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha,
+                                      static_cast<float*>(y), ldy, stream);
+}
+
+}  // namespace arcq

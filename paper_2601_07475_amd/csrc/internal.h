@@ -42,6 +42,13 @@ arcq_status launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
                         void* y, int y_dtype, int64_t ldy,
                         void* workspace, size_t workspace_bytes, hipStream_t stream);
 
+// Tiled kernel whose waves split every stage along k inside the workgroup (gemm_ksplit.hip): which of its tile
+// shapes serves this problem (0: none), and its launch.
+int gemm_ksplit_variant(int64_t M, int64_t N, int64_t Kp);
+arcq_status launch_gemm_ksplit(int variant, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
+                               const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, float alpha, void* y, int y_dtype,
+                               int64_t ldy, hipStream_t stream);
+
 arcq_status launch_probe_mfma_f16(int iters, float* sink, double* flop_host, hipStream_t stream);
 arcq_status launch_probe_mfma_fp4(int iters, float* sink, double* flop_host, hipStream_t stream);
 arcq_status launch_ref_gemm_bf16(const void* x, const void* w, int64_t M, int64_t N, int64_t K, _Float16* y, int64_t ldy,

@@ -284,6 +284,9 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     # 65 to 128 rows with enough weights for the tiled kernels with split K instead of the weight-streaming kernel
     # (K' >= 4096 with 2 * 10^7 weights, K' >= 8192 with 1.2 * 10^7)
     (100, 4800, 4096, 256), (128, 1500, 8192, 512),
+    # between 144 and 256 tiles of 64 x 64, 128 x 64 or 128 x 128 and K' a multiple of 256: the kernel whose waves split
+    # every stage into k quarters inside the workgroup (ragged edges in both directions; two, five and 17 stages)
+    (130, 3100, 512, 0), (192, 4096, 4096, 256), (300, 3500, 1024, 256), (700, 3900, 448, 64), (1024, 4096, 1024, 256),
 ]
 
 
