@@ -156,7 +156,8 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
     constexpr int G = WM + WN;                 // fragments per k-step
-    constexpr int P = WM * WN;                 // MFMAs per k-step, one per group
+    constexpr int MPG = (WM * WN >= 16) ? 2 : 1;   // MFMAs per group (singles spill with 4 x 4 fragments)
+    constexpr int P = WM * WN / MPG;           // groups per k-step: after every group the decode of G / P fragments
     uint4 ca[WM], cw[WN];
     uint32_t sa[WM], sw[WN];
     half8 fa[2][WM], fw[2][WN];
@@ -209,9 +210,12 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
 #pragma unroll
                 for (int gidx = (p * G) / P; gidx < ((p + 1) * G) / P; ++gidx) decode_frag(gidx, (t + 1) & 3);
                 __builtin_amdgcn_sched_barrier(0);
-                const int i = p / WN, j = p % WN;
-                // weights as the row operand: see store_fragment
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[t & 1][j], fa[t & 1][i], acc[i][j], 0, 0, 0);
+#pragma unroll
+                for (int q = MPG * p; q < MPG * p + MPG; ++q) {
+                    const int i = q / WN, j = q % WN;
+                    // weights as the row operand: see store_fragment
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[t & 1][j], fa[t & 1][i], acc[i][j], 0, 0, 0);
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 if (t < 3) {
 #pragma unroll
