@@ -160,7 +160,9 @@ arcq_status arcq_gemm_workspace_size(int64_t M, int64_t N, int64_t Kp, size_t* b
  * with fp32 accumulation.  Operands are decoded exactly (every code*scale
  * product fits fp16) and multiplied on the fp16 MFMA path.
  * a_*  packed activations [M, Kp] from arcq_quantize_act;  w_*  packed weights [N, Kp]
- *      from arcq_pack_weight; codes 8-byte aligned.  Kp % 16 == 0, Kp > 0.
+ *      from arcq_pack_weight; codes 8-byte aligned.  Kp % 16 == 0, Kp > 0.  Every such Kp and alignment runs
+ *      on the tiled / weight-streaming kernels; Kp % 64 == 0 with 16-byte aligned codes and 4-byte aligned
+ *      scales additionally lets the tiled kernels copy straight into LDS (up to 1.35x faster on large M).
  * y    out [M, N] row-major, pitch ldy elements (ldy >= N), y_dtype ARCQ_DTYPE_F16 / _F32,
  *      4-byte aligned (16-byte aligned with ldy % 8 == 0 lets the tiled kernels store whole lines).
  * workspace  device scratch of at least arcq_gemm_workspace_size bytes, 256-byte

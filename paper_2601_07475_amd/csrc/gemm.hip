@@ -171,7 +171,14 @@ struct StagedCfg {
     static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
 };
 
-template <int WM, int WN, int GM, int GN, typename OutT>
+//
+// REG: the same tiles, LDS layout and compute schedule for operands the direct-to-LDS copies cannot serve: any
+// number of blocks per row (K' a multiple of 16 only) and rows that are only 8-byte aligned.  A thread fetches
+// its pieces of a stage into registers (loads declared with the alignment the interface guarantees, 8 bytes
+// for codes and 1 for scale bytes), all at once right after the barrier that opens
+// stage s+1, and writes them to LDS seven k-steps later, just before the barrier that opens the stage they
+// belong to, with blocks past the end of the row replaced by zeros: every stage is then a whole stage.
+template <int WM, int WN, int GM, int GN, typename OutT, bool REG = false>
 __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N,
@@ -211,8 +218,8 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     // When K' is an odd multiple of 64 the last stage is half a stage (4 blocks): the lanes that
     // would fetch its missing second half re-fetch the first half instead (never used), which
     // keeps every access inside the operand.  `half` selects those adjusted offsets.
-    const bool has_half = (nbk & 7) != 0;
-    const int nstage = (nbk >> 3) + (has_half ? 1 : 0);        // of the whole reduction dimension
+    const bool has_half = !REG && (nbk & 7) != 0;
+    const int nstage = REG ? (nbk + 7) >> 3 : (nbk >> 3) + (has_half ? 1 : 0);   // of the whole reduction dimension
     const int per_split = nstage / splits, extra = nstage % splits;
     const int s_begin = split * per_split + min(split, extra);  // this workgroup's stages [s_begin, s_end)
     const int s_end = s_begin + per_split + (split < extra ? 1 : 0);
@@ -255,6 +262,49 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
     auto issue_all = [&](int stage, int buf) {
 #pragma unroll
         for (int d = 0; d < C::NDMA; ++d) issue_one(d, stage, buf);
+    };
+    // ---- REG: the same pieces through registers (piece d of a thread lands where DMA instruction d puts it).
+    // A piece that would reach past the end of its row is fetched from further left, so that it ends with the row
+    // (needs nbk >= 4), and shifted into place when it is written to LDS.
+    constexpr int NCP = C::NA + C::NW, NSP = C::NAS + C::NWS;
+    uint4 rc[REG ? NCP : 1];
+    uint32_t rs[REG ? NSP : 1];
+    auto reg_issue = [&](int stage) {
+        const uint32_t oc = 8u * (uint32_t)min(8 * stage + 2 * (int)lp_, nbk - 2);
+#pragma unroll
+        for (int d = 0; d < NCP; ++d) {
+            const bool is_a = d < C::NA;
+            const int p = is_a ? d : d - C::NA;
+            const uint32_t row = (uint32_t)(is_a ? min(wg_m0 + p * (C::NT / 4) + crow, M - 1) : min(wg_n0 + p * (C::NT / 4) + crow, N - 1));
+            rc[d] = load16_a8((is_a ? a_codes : w_codes) + (size_t)(row * cpitch32 + oc));
+        }
+        const uint32_t os = (uint32_t)min(8 * stage + 4 * (tid & 1), nbk - 4);
+#pragma unroll
+        for (int d = 0; d < NSP; ++d) {
+            const bool is_a = d < C::NAS;
+            const int p = is_a ? d : d - C::NAS;
+            const uint32_t row = (uint32_t)(is_a ? min(wg_m0 + p * (C::NT / 2) + srow, M - 1) : min(wg_n0 + p * (C::NT / 2) + srow, N - 1));
+            rs[d] = load4_a1((is_a ? a_scales : w_scales) + (size_t)(row * spitch32 + os));
+        }
+    };
+    auto reg_commit = [&](int stage, int buf) {
+        uint8_t* st = lds + buf * C::STAGE_BYTES;
+        const int b0 = 8 * stage + 2 * (int)lp_;       // this piece: blocks b0, b0 + 1
+        const bool both = b0 + 1 < nbk, one = b0 < nbk;
+#pragma unroll
+        for (int d = 0; d < NCP; ++d) {
+            const uint4 v = uint4{both ? rc[d].x : one ? rc[d].z : 0u, both ? rc[d].y : one ? rc[d].w : 0u, both ? rc[d].z : 0u, both ? rc[d].w : 0u};
+            const int at = d < C::NA ? C::A_CODES + 16 * (d * C::NT + tid) : C::W_CODES + 16 * ((d - C::NA) * C::NT + tid);
+            *reinterpret_cast<uint4*>(st + at) = v;
+        }
+        const int sb0 = 8 * stage + 4 * (tid & 1);      // this word: blocks sb0 .. sb0 + 3
+        const int skip = sb0 - min(sb0, nbk - 4);       // bytes of the fetched word that belong to earlier blocks
+#pragma unroll
+        for (int d = 0; d < NSP; ++d) {
+            const uint32_t word = skip >= 4 ? 0u : rs[d] >> (8 * skip);
+            const int at = d < C::NAS ? C::A_SCALES + 4 * (d * C::NT + tid) : C::W_SCALES + 4 * ((d - C::NAS) * C::NT + tid);
+            *reinterpret_cast<uint32_t*>(st + at) = word;
+        }
     };
 
     // ---- LDS read offsets of this lane inside a stage.  Fragment i of a wave is 32 rows (2048
@@ -346,9 +396,12 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
             if (x == 6) {
                 // stage s+1 must have landed: the copies of the DIST - 1 later stages are younger, and
                 // everything older has retired once at most that many operations are outstanding
-                wait_vmcnt<(C::DIST - 1) * C::NDMA>();
+                // (REG: this wave's LDS writes of stage s+1 must have completed)
+                if constexpr (REG) wait_lgkmcnt0();
+                else wait_vmcnt<(C::DIST - 1) * C::NDMA>();
                 wg_barrier();
                 read_raw(0, lds + buf1 * C::STAGE_BYTES);
+                if constexpr (REG) reg_issue(min(s + 2, s_end - 1));
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -366,25 +419,37 @@ __global__ __launch_bounds__(64 * GM * GN) void gemm_staged_kernel(
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[x & 1][j], fa[x & 1][i], acc[i][j], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (FULL && x < 6) {            // copies of stage s + NSTAGE - 1, spread over steps 0..5
+                if (!REG && FULL && x < 6) {    // copies of stage s + NSTAGE - 1, spread over steps 0..5
 #pragma unroll
                     for (int d = 0; d < C::NDMA; ++d)
                         if ((d * 6) / C::NDMA == x && (d - (x * C::NDMA + 5) / 6) == p) issue_one(d, fetch, buf2);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            if constexpr (REG)
+                if (x == 5) {                   // stage s+1, fetched since step 6 of the stage before
+                    reg_commit(min(s + 1, s_end - 1), buf1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
         }
         buf = buf1;
     };
 
+    if constexpr (REG) {
+        reg_issue(s_begin);
+        reg_commit(s_begin, 0);
+        reg_issue(min(s_begin + 1, s_end - 1));
+        wait_lgkmcnt0();
+    } else {
 #pragma unroll
-    for (int d = 0; d < C::DIST; ++d) issue_all(min(s_begin + d, s_end - 1), d);
-    wait_vmcnt<(C::DIST - 1) * C::NDMA>();
+        for (int d = 0; d < C::DIST; ++d) issue_all(min(s_begin + d, s_end - 1), d);
+        wait_vmcnt<(C::DIST - 1) * C::NDMA>();
+    }
     wg_barrier();
     read_raw(0, lds);
 #pragma unroll
     for (int gidx = 0; gidx < G; ++gidx) decode_frag(gidx, 0);
-    const int nfull = nbk >> 3;
+    const int nfull = REG ? nstage : nbk >> 3;
     for (int s = s_begin; s < min(s_end, nfull); ++s) run_stage(s, std::integral_constant<int, 8>{});
     if (has_half && s_end == nstage) run_stage(nfull, std::integral_constant<int, 4>{});
     wait_vmcnt<0>();                            // no copy may still be in flight when the LDS is released
@@ -646,7 +711,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     }
 }
 
-template <int WM, int WN, int GM, int GN, typename OutT>
+template <int WM, int WN, int GM, int GN, bool REG = false, typename OutT>
 arcq_status launch_staged(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                           const uint8_t* w_scales, int M, int N, int nbk, float alpha, OutT* y, int64_t ldy,
                           hipStream_t stream, int splits = 1, float* partial = nullptr) {
@@ -654,7 +719,7 @@ arcq_status launch_staged(const uint8_t* a_codes, const uint8_t* a_scales, const
     const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
     if (splits > 1) {
         // fp32 partial results [splits, M, N] in the workspace, then one pass that adds them
-        auto kern = gemm_staged_kernel<WM, WN, GM, GN, float>;
+        auto kern = gemm_staged_kernel<WM, WN, GM, GN, float, REG>;
         static std::atomic<uint64_t> lds_raised{0};
         if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
         const int64_t stride = (int64_t)M * N;
@@ -664,7 +729,7 @@ arcq_status launch_staged(const uint8_t* a_codes, const uint8_t* a_scales, const
         return launch_splitk_reduce(partial, splits, M, N, alpha, y, std::is_same<OutT, _Float16>::value ? ARCQ_DTYPE_F16 : ARCQ_DTYPE_F32,
                                     ldy, stream);
     }
-    auto kern = gemm_staged_kernel<WM, WN, GM, GN, OutT>;
+    auto kern = gemm_staged_kernel<WM, WN, GM, GN, OutT, REG>;
     static std::atomic<uint64_t> lds_raised{0};
     if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales, w_codes,
@@ -713,6 +778,11 @@ __device__ __forceinline__ void transpose_scale_pairs(uint2 s, uint32_t& even_ch
     odd_chunks = t[1];
 }
 
+// Rows need not start on 16-byte boundaries (K' / 16 odd, or operands that are only 8-byte aligned): every load
+// is declared with the alignment the interface guarantees (codes 8 bytes, scale bytes 1), which the memory
+// path serves in one request like an aligned one.  With an odd number of blocks the last block of a row has no
+// partner: the pairs of the main loops stop before it and the last wave handles it by itself at the end, with
+// 8-byte loads.
 template <int MT, int NT, int WAVES, int U, bool GRP, typename OutT>
 __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
@@ -763,15 +833,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     auto load_group = [&](int g, Group& G) {
         const int64_t co = 256 * (int64_t)g + 16 * q, so = 32 * (int64_t)g + 8 * q;
 #pragma unroll
-        for (int r = 0; r < MT; ++r) G.sa2[r] = *reinterpret_cast<const uint2*>(as[r] + so);
+        for (int r = 0; r < MT; ++r) G.sa2[r] = load8_a1(as[r] + so);
 #pragma unroll
-        for (int t = 0; t < NT; ++t) G.sw2[t] = *reinterpret_cast<const uint2*>(ws[t] + so);
+        for (int t = 0; t < NT; ++t) G.sw2[t] = load8_a1(ws[t] + so);
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
 #pragma unroll
-            for (int r = 0; r < MT; ++r) G.ca[m][r] = *reinterpret_cast<const uint4*>(ac[r] + co + 64 * m);
+            for (int r = 0; r < MT; ++r) G.ca[m][r] = load16_a8(ac[r] + co + 64 * m);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) G.cw[m][t] = *reinterpret_cast<const uint4*>(wc[t] + co + 64 * m);
+            for (int t = 0; t < NT; ++t) G.cw[m][t] = load16_a8(wc[t] + co + 64 * m);
         }
     };
     auto compute_group = [&](const Group& G) {
@@ -807,32 +877,31 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             }
         }
     };
-    // the lane's two blocks 8c + 2q, 8c + 2q + 1 of chunk c exist (nbk is even) or lie past the end of the row: then
-    // the lane reads the start of its row instead and both operands count as zero (codes and scale bytes, so that
-    // no stray scale pattern meets a zero).  The zeroing happens at the use, not at the load: a select behind a
-    // load would make the wave wait for it at once.
+    // the lane's two blocks 8c + 2q, 8c + 2q + 1 of chunk c both exist, or the pair counts as zero (codes and scale
+    // bytes, so that no stray scale pattern meets a zero) and the lane reads the start of its row instead.  The
+    // zeroing happens at the use, not at the load: a select behind a load would make the wave wait for it at once.
     auto load_chunks = [&](int c0, Chunks& T) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int c = c0 + u;
-            const bool ok = 8 * c + 2 * q < nbk;
-            const int64_t co = ok ? 64 * (int64_t)c + 16 * q : 0, so = ok ? 8 * (int64_t)c + 2 * q : 0;
+            const int b0 = 8 * (c0 + u) + 2 * q;
+            const bool ok = b0 + 1 < nbk;
+            const int64_t co = ok ? 8 * (int64_t)b0 : 0, so = ok ? b0 : 0;
 #pragma unroll
             for (int r = 0; r < MT; ++r) {
-                T.ca[u][r] = *reinterpret_cast<const uint4*>(ac[r] + co);
-                T.sa[u][r] = *reinterpret_cast<const uint16_t*>(as[r] + so);
+                T.ca[u][r] = load16_a8(ac[r] + co);
+                T.sa[u][r] = load2_a1(as[r] + so);
             }
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                T.cw[u][t] = *reinterpret_cast<const uint4*>(wc[t] + co);
-                T.sw[u][t] = *reinterpret_cast<const uint16_t*>(ws[t] + so);
+                T.cw[u][t] = load16_a8(wc[t] + co);
+                T.sw[u][t] = load2_a1(ws[t] + so);
             }
         }
     };
     auto compute_chunks = [&](int c0, const Chunks& T) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const bool ok = 8 * (c0 + u) + 2 * q < nbk;
+            const bool ok = 8 * (c0 + u) + 2 * q + 1 < nbk;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 half8 fa[MT];
@@ -852,10 +921,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             }
         }
     };
-
     bool grouped = false;
-    if constexpr (GRP)
-        grouped = (nbk & 7) == 0 && ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 7) == 0;
+    if constexpr (GRP) grouped = nbk >= 32;
     if (grouped) {
         // Whole chunks in groups of four, dealt round-robin to the waves; the up to three chunks behind the last
         // group go to the waves that took one group less.  With one group per wave and four tiles (the up-projection
@@ -881,6 +948,34 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
             Chunks T;
             load_chunks(c0, T);
             compute_chunks(c0, T);
+        }
+    }
+    // the last block of a row with an odd number of blocks: lane group 0 supplies its two octets, the others zeros
+    if ((nbk & 1) != 0 && wave == WAVES - 1) {
+        uint2 oa[MT], ow[NT];
+        uint32_t osa[MT], osw[NT];
+#pragma unroll
+        for (int r = 0; r < MT; ++r) {
+            oa[r] = load8_a8(ac[r] + 8 * (int64_t)(nbk - 1));
+            osa[r] = as[r][nbk - 1];
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            ow[t] = load8_a8(wc[t] + 8 * (int64_t)(nbk - 1));
+            osw[t] = ws[t][nbk - 1];
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            half8 fa[MT];
+#pragma unroll
+            for (int r = 0; r < MT; ++r) fa[r] = decode8(q ? 0u : k ? oa[r].y : oa[r].x, scale_pair(q ? 0u : osa[r]));
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const half8 fw = decode8(q ? 0u : k ? ow[t].y : ow[t].x, scale_pair(q ? 0u : osw[t]));
+#pragma unroll
+                for (int r = 0; r < MT; ++r)
+                    acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[r], fw, acc[r][t], 0, 0, 0);
+            }
         }
     }
 #pragma unroll
@@ -929,7 +1024,7 @@ static bool skinny_shape(int64_t M, int64_t N, int64_t Kp) {
 // write and read of the fp32 partial results at about 3 TB/s.
 int split_k(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nbk = Kp >> 4;
-    if (skinny_shape(M, N, Kp) || (nbk & 3) != 0 || nbk < 8) return 1;
+    if (skinny_shape(M, N, Kp) || nbk < 8) return 1;
     if (gemm_ksplit_variant(M, N, Kp) != 0) return 1;      // the k split happens inside the workgroups
     if (((M + 255) / 256) * ((N + 255) / 256) >= 256 || ((M + 127) / 128) * ((N + 255) / 256) >= 192) return 1;
     const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
@@ -955,9 +1050,7 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
                          const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, float alpha, OutT* y,
                          int64_t ldy, float* workspace, hipStream_t stream) {
     const int nbk = (int)(Kp >> 4);
-    if (skinny_shape(M, N, Kp) && (nbk & 1) == 0 &&
-        ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
-        ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 1) == 0) {
+    if (skinny_shape(M, N, Kp)) {
         // Weight-streaming path.  Enough waves to keep the weight stream in flight, as few as that allows
         // so that each wave has several KB to request at once: with many weight rows several tiles per
         // wave share the activation operand; with few, one tile per wave so that every CU still gets a
@@ -1017,6 +1110,13 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
         }
         return launch_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream,
                                          split_k(M, N, Kp), workspace);
+    }
+    if (offsets_fit && nbk >= 8) {
+        // any K' that is a multiple of 16, operands that are only 8-byte aligned: stages through registers
+        if (((M + 127) / 128) * ((N + 255) / 256) >= 192)
+            return launch_staged<2, 2, 2, 4, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+        return launch_staged<2, 2, 2, 2, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream,
+                                               split_k(M, N, Kp), workspace);
     }
     dim3 grid((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128));
     hipLaunchKernelGGL(gemm_direct_kernel<OutT>, grid, dim3(256), 0, stream, a_codes, a_scales, w_codes, w_scales,

@@ -46,4 +46,27 @@ __device__ __forceinline__ half8 decode8_half(uint32_t c, uint32_t halves, int h
     return out;
 }
 
+// Loads with the alignment the interface guarantees rather than that of their size (codes: 8 bytes; scale bytes: 1).
+// Global memory serves them in one request whatever the address; declaring the alignment keeps the access defined.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef u32x4 u32x4_a8 __attribute__((aligned(8)));
+typedef u32x2 u32x2_a1 __attribute__((aligned(1)));
+typedef uint32_t u32_a1 __attribute__((aligned(1)));
+typedef uint16_t u16_a1 __attribute__((aligned(1)));
+__device__ __forceinline__ uint4 load16_a8(const uint8_t* p) {
+    const u32x4 v = *reinterpret_cast<const u32x4_a8*>(p);
+    return uint4{v[0], v[1], v[2], v[3]};
+}
+__device__ __forceinline__ uint2 load8_a8(const uint8_t* p) {
+    const u32x2 v = *reinterpret_cast<const u32x2*>(p);
+    return uint2{v[0], v[1]};
+}
+__device__ __forceinline__ uint2 load8_a1(const uint8_t* p) {
+    const u32x2 v = *reinterpret_cast<const u32x2_a1*>(p);
+    return uint2{v[0], v[1]};
+}
+__device__ __forceinline__ uint32_t load4_a1(const uint8_t* p) { return *reinterpret_cast<const u32_a1*>(p); }
+__device__ __forceinline__ uint32_t load2_a1(const uint8_t* p) { return *reinterpret_cast<const u16_a1*>(p); }
+
 }  // namespace arcq

@@ -287,6 +287,14 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     # between 144 and 256 tiles of 64 x 64, 128 x 64 or 128 x 128 and K' a multiple of 256: the kernel whose waves split
     # every stage into k quarters inside the workgroup (ragged edges in both directions; two, five and 17 stages)
     (130, 3100, 512, 0), (192, 4096, 4096, 256), (300, 3500, 1024, 256), (700, 3900, 448, 64), (1024, 4096, 1024, 256),
+    # K' with an odd number of blocks, or K' % 64 = 32 (S is any multiple of 16): rows that start 8 bytes off a 16-byte
+    # boundary.  Weight-streaming kernel with 1, 2, 4 and 8 row tiles, one block per row, last chunk of 1, 3, 5, 7 blocks
+    (8, 40, 16, 0), (1, 300, 1008, 0), (16, 1000, 4096, 272), (16, 4097, 1008, 48), (33, 77, 2048, 2000), (20, 300, 512, 48),
+    (64, 4097, 240, 64), (100, 260, 4160, 80), (128, 45, 160, 16), (17, 14336, 512, 496),
+    # the same on the tiled kernels, stages through registers: 128 x 128 tiles without and with split K' (the last stage
+    # holds 2, 7, 1 and 4 blocks), 128 x 256 tiles, and a large output
+    (257, 131, 1040, 16), (200, 140, 560, 64), (300, 260, 4160, 80), (256, 512, 4096, 320), (1990, 4070, 240, 64),
+    (2048, 3000, 1024, 144), (4000, 4100, 112, 64), (128, 1500, 8192, 528),
 ]
 
 
@@ -299,6 +307,32 @@ def test_gemm_parity(M, N, K, S, dtype):
     wc, wsc = A.pack_weight(c["W"], c["perm"], S, c["sT_w"])
     Yref = A.gemm(ac, asc, c["sT_x"], wc, wsc, c["sT_w"])
     Y = B.arcq_gemm(dev(ac), dev(asc), c["sT_x"], dev(wc), dev(wsc), c["sT_w"], out_dtype=dtype)
+    torch.cuda.synchronize()
+    err = norm_err(Y.float().cpu().numpy(), Yref)
+    say(f"   normalised max error {err:.3e}")
+    assert err <= (GEMM_TOL_F16 if dtype == torch.float16 else GEMM_TOL_F32)
+
+
+@pytest.mark.parametrize("M,N,Kp", [(16, 1000, 1024), (64, 300, 4352), (300, 260, 1024), (192, 4096, 1024), (2048, 3000, 256)])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+def test_gemm_operands_only_8_byte_aligned(M, N, Kp, dtype):
+    """Codes 8 bytes off a 16-byte boundary and scale bytes at odd addresses: the least the interface asks for."""
+    say(f"gemm with 8-byte aligned operands M={M} N={N} K'={Kp} {dtype}")
+    rng = np.random.default_rng(M + N + Kp)
+    ac = rng.integers(0, 256, (M, Kp // 2), dtype=np.uint8)
+    wc = rng.integers(0, 256, (N, Kp // 2), dtype=np.uint8)
+    asc = rng.integers(0x20, 0x50, (M, Kp // 16), dtype=np.uint8)
+    wsc = rng.integers(0x20, 0x50, (N, Kp // 16), dtype=np.uint8)
+    Yref = A.gemm(ac, asc, np.float32(0.5), wc, wsc, np.float32(0.25))
+
+    def shifted(a, by):
+        buf = torch.zeros(a.size + 256, dtype=torch.uint8, device="cuda")
+        start = (-buf.data_ptr()) % 16 + by
+        view = buf[start:start + a.size].view(a.shape)
+        view.copy_(torch.from_numpy(a))
+        assert view.data_ptr() % 16 == by % 16
+        return view
+    Y = B.arcq_gemm(shifted(ac, 8), shifted(asc, 3), 0.5, shifted(wc, 8), shifted(wsc, 1), 0.25, out_dtype=dtype)
     torch.cuda.synchronize()
     err = norm_err(Y.float().cpu().numpy(), Yref)
     say(f"   normalised max error {err:.3e}")
