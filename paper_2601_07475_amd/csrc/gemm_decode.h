@@ -58,6 +58,11 @@ __device__ __forceinline__ uint4 load16_a8(const uint8_t* p) {
     const u32x4 v = *reinterpret_cast<const u32x4_a8*>(p);
     return uint4{v[0], v[1], v[2], v[3]};
 }
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+__device__ __forceinline__ uint4 load16_a4(const uint8_t* p) {
+    const u32x4 v = *reinterpret_cast<const u32x4_a4*>(p);
+    return uint4{v[0], v[1], v[2], v[3]};
+}
 __device__ __forceinline__ uint2 load8_a8(const uint8_t* p) {
     const u32x2 v = *reinterpret_cast<const u32x2*>(p);
     return uint2{v[0], v[1]};

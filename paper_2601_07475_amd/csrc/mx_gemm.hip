@@ -9,6 +9,7 @@
 // No decode: packed operands go global -> LDS -> registers -> matrix core unchanged.
 #include "gemm_epilogue.h"
 #include "internal.h"
+#include "gemm_decode.h"
 #include "lds_dma.h"
 
 #include <type_traits>
@@ -303,12 +304,13 @@ __global__ __launch_bounds__(256) void mx_gemm_direct_kernel(
     store_tile_swapped<2, 2>(acc, m0, n0, r, h, M, N, 1.0f, y, ldy, false);
 }
 
-// Weight-streaming kernel for M <= 64 (decode, batched decode) and K' % 128 == 0: bound by
+// Weight-streaming kernel for M <= 64 (decode, batched decode), any K' (a multiple of 32): bound by
 // reading the packed weights once (17/32 byte per weight).  v_mfma_scale_f32_16x16x128_f8f6f4: lane
 // (i = lane % 16, q = lane / 16) supplies the 32 values of block 4c + q of row i for the 128-k chunk c,
 // with that block's scale byte.  A lane loads 16 bytes of codes per row and chunk (a wave: 16 rows x 64
-// contiguous bytes) and the 4 scale bytes of the chunk (the four lanes of a row load the same word and
-// each extracts its own byte).  MT tiles of 16 activation rows share every weight fragment; the WAVES
+// contiguous bytes) and its block's scale byte.  Blocks past the end of a row (a last chunk of one to three
+// blocks) count as zero codes.  Loads are declared with the alignment the interface guarantees (codes 4 bytes,
+// scale bytes 1); global memory serves them in one request at any address.  MT tiles of 16 activation rows share every weight fragment; the WAVES
 // waves of a workgroup split K' and add their partial tiles through LDS.  Everything is loaded straight
 // into registers; latency is hidden by occupancy.
 typedef float float4v __attribute__((ext_vector_type(4)));
@@ -338,20 +340,20 @@ __global__ __launch_bounds__(WAVES * 64) void mx_gemm_skinny_kernel(
     const int i = lane & 15, q = lane >> 4;
     const int n0 = blockIdx.x * (16 * NT);
     const int64_t cpitch = (int64_t)nb * 16, spitch = nb;
-    const int nchunk = nb >> 2;                                  // nb % 4 == 0 on this path
+    const int nchunk = (nb + 3) >> 2;                            // the last chunk may hold fewer than four blocks
 
     const uint8_t *ac[MT], *as[MT];
 #pragma unroll
     for (int r = 0; r < MT; ++r) {
         const int m = min(16 * r + i, M - 1);                    // rows past M repeat row M-1 and are not stored
-        ac[r] = a_codes + (int64_t)m * cpitch + 16 * q;
+        ac[r] = a_codes + (int64_t)m * cpitch;
         as[r] = a_scales + (int64_t)m * spitch;
     }
     const uint8_t *wc[NT], *ws[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int n = min(n0 + 16 * t + i, N - 1);
-        wc[t] = w_codes + n * cpitch + 16 * q;
+        wc[t] = w_codes + n * cpitch;
         ws[t] = w_scales + n * spitch;
     }
     float4v acc[MT][NT];
@@ -362,7 +364,7 @@ __global__ __launch_bounds__(WAVES * 64) void mx_gemm_skinny_kernel(
 
     int cbase = 0, first_wave = 0;              // first chunk and first wave of the chunk-at-a-time loop
     if constexpr (GRP) {
-        const int ngroup = nchunk >> 2;         // groups of four chunks
+        const int ngroup = nb >> 4;             // groups of four whole chunks
         const uint32_t sel_half = q < 2 ? 0x05040100u : 0x07060302u;
         const uint32_t sel_byte = (q & 1) ? 0x07030501u : 0x06020400u;
         for (int g = wave; g < ngroup; g += WAVES) {
@@ -372,15 +374,15 @@ __global__ __launch_bounds__(WAVES * 64) void mx_gemm_skinny_kernel(
             // in issue order: asked for first, they do not make the wave wait for the whole group's codes; the
             // scheduling barrier keeps every load of the group ahead of its first use
 #pragma unroll
-            for (int r = 0; r < MT; ++r) sa[r] = *reinterpret_cast<const uint32_t*>(as[r] + 16 * (int64_t)g + 4 * q);
+            for (int r = 0; r < MT; ++r) sa[r] = load4_a1(as[r] + 16 * (int64_t)g + 4 * q);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) sw[t] = *reinterpret_cast<const uint32_t*>(ws[t] + 16 * (int64_t)g + 4 * q);
+            for (int t = 0; t < NT; ++t) sw[t] = load4_a1(ws[t] + 16 * (int64_t)g + 4 * q);
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
 #pragma unroll
-                for (int r = 0; r < MT; ++r) ca[m][r] = *reinterpret_cast<const uint4*>(ac[r] + 256 * (int64_t)g + 64 * m);
+                for (int r = 0; r < MT; ++r) ca[m][r] = load16_a4(ac[r] + 256 * (int64_t)g + 64 * m + 16 * q);
 #pragma unroll
-                for (int t = 0; t < NT; ++t) cw[m][t] = *reinterpret_cast<const uint4*>(wc[t] + 256 * (int64_t)g + 64 * m);
+                for (int t = 0; t < NT; ++t) cw[m][t] = load16_a4(wc[t] + 256 * (int64_t)g + 64 * m + 16 * q);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -413,36 +415,34 @@ __global__ __launch_bounds__(WAVES * 64) void mx_gemm_skinny_kernel(
         uint32_t sa[U][MT], sw[U][NT];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            // chunks past the end re-read the last one and count as zero (codes zeroed, scale byte of 1.0)
-            const bool ok = c0 + u < nchunk;
-            const int64_t c = ok ? c0 + u : nchunk - 1;
+            // a block past the end of the row: the lane re-reads block 0 and the block counts as zero (codes zeroed where
+            // they are used, not here: a select behind a load would make the wave wait for it at once)
+            const int64_t b = 4 * (c0 + u) + q < nb ? 4 * (c0 + u) + q : 0;
 #pragma unroll
             for (int r = 0; r < MT; ++r) {
-                ca[u][r] = *reinterpret_cast<const uint4*>(ac[r] + 64 * c);
-                sa[u][r] = *reinterpret_cast<const uint32_t*>(as[r] + 4 * c);
-                if (!ok) { ca[u][r] = make_uint4(0, 0, 0, 0); sa[u][r] = 0x7F7F7F7Fu; }
+                ca[u][r] = load16_a4(ac[r] + 16 * b);
+                sa[u][r] = as[r][b];
             }
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                cw[u][t] = *reinterpret_cast<const uint4*>(wc[t] + 64 * c);
-                sw[u][t] = *reinterpret_cast<const uint32_t*>(ws[t] + 4 * c);
-                if (!ok) { cw[u][t] = make_uint4(0, 0, 0, 0); sw[u][t] = 0x7F7F7F7Fu; }
+                cw[u][t] = load16_a4(wc[t] + 16 * b);
+                sw[u][t] = ws[t][b];
             }
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
+            const bool ok = 4 * (c0 + u) + q < nb;
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                const int8v vw = {(int)cw[u][t].x, (int)cw[u][t].y, (int)cw[u][t].z, (int)cw[u][t].w, 0, 0, 0, 0};
-                const int bw = (int)((sw[u][t] >> (8 * q)) & 0xFFu);
+                const int8v vw = {ok ? (int)cw[u][t].x : 0, ok ? (int)cw[u][t].y : 0, ok ? (int)cw[u][t].z : 0, ok ? (int)cw[u][t].w : 0, 0, 0, 0, 0};
 #pragma unroll
                 for (int r = 0; r < MT; ++r) {
-                    const int8v va = {(int)ca[u][r].x, (int)ca[u][r].y, (int)ca[u][r].z, (int)ca[u][r].w, 0, 0, 0, 0};
-                    const int ba = (int)((sa[u][r] >> (8 * q)) & 0xFFu);
+                    const int8v va = {ok ? (int)ca[u][r].x : 0, ok ? (int)ca[u][r].y : 0, ok ? (int)ca[u][r].z : 0, ok ? (int)ca[u][r].w : 0, 0, 0, 0, 0};
                     // activations as the 16-row operand: lane holds column n = lane % 16, register e row 4 (lane / 16) + e
-                    acc[r][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(va, vw, acc[r][t], 4, 4, 0, ba, 0, bw);
+                    acc[r][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(va, vw, acc[r][t], 4, 4, 0, (int)sa[u][r], 0, (int)sw[u][t]);
                 }
             }
+        }
     }
 #pragma unroll
     for (int r = 0; r < MT; ++r)
@@ -501,9 +501,8 @@ arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, co
 // pipeline fill and the second launch (fitted to measurements over N = 2048 .. 8192, K' = 4352 .. 29696).
 int mx_split_k(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nb = Kp >> 5;
-    if ((nb & 3) != 0) return 1;
     const bool streaming = M <= 32 ? N * Kp < 200000000 : M <= 64 && N < 8192;
-    if (streaming) return 1;
+    if (streaming || (nb & 3) != 0) return 1;
     if (((M + 255) / 256) * ((N + 255) / 256) >= 256 || ((M + 127) / 128) * ((N + 255) / 256) >= 192) return 1;
     const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
     const int64_t nunit = (nb + 7) >> 3;
@@ -535,7 +534,7 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
     // K' = 2176 .. 14592, M = 16 .. 128: on the FP4 instruction a 128- or 256-row tile costs no more than a
     // 16-row one, so the tiled kernels win as soon as their tiles fill the chip; above 64 rows they always did).
     const bool streaming = M <= 32 ? N * Kp < 200000000 : M <= 64 && N < 8192;
-    if (streaming && (nb & 3) == 0 && aligned16) {
+    if (streaming) {
         const int64_t tiles = (N + 15) / 16;
 #define ARCQ_MX_SKINNY(MT_, NT_, W_, U_) \
     return launch_mx_skinny<MT_, NT_, W_, U_>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream)

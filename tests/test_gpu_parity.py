@@ -631,6 +631,9 @@ MX_GEMM_SHAPES = [  # M, N, K, S: fallback kernel (K' % 128 != 0), every staged 
     # where the tiled kernels take over from the weight-streaming one: 33 to 64 rows with at least 8192 weight rows
     # (and just below), more than 64 rows
     (48, 8200, 480, 32), (48, 8100, 480, 32), (65, 300, 992, 32),
+    # weight-streaming kernel with K' % 128 != 0: a last chunk of 1, 2 or 3 blocks, rows shorter than a chunk
+    (8, 40, 96, 0), (3, 17, 32, 32), (20, 300, 512, 160), (33, 77, 2048, 2016), (64, 4097, 256, 96), (1, 4096, 14336, 288),
+    (17, 14336, 512, 480),
 ]
 
 
@@ -647,6 +650,30 @@ def test_mx_gemm_parity(M, N, K, S, dtype):
     err = norm_err(Y.float().cpu().numpy(), Yref)
     say(f"   normalised max error {err:.3e}")
     assert err <= (GEMM_TOL_F16 if dtype == torch.float16 else GEMM_TOL_F32)
+
+
+@pytest.mark.parametrize("M,N,Kp", [(16, 1000, 1024), (64, 300, 4384)])
+def test_mx_gemm_operands_only_4_byte_aligned(M, N, Kp):
+    """Codes 4 bytes off a 16-byte boundary and scale bytes at odd addresses: the least the interface asks for."""
+    say(f"mx_gemm with 4-byte aligned operands M={M} N={N} K'={Kp}")
+    rng = np.random.default_rng(M + N + Kp)
+    ac = rng.integers(0, 256, (M, Kp // 2), dtype=np.uint8)
+    wc = rng.integers(0, 256, (N, Kp // 2), dtype=np.uint8)
+    asc = rng.integers(120, 134, (M, Kp // 32), dtype=np.uint8)
+    wsc = rng.integers(120, 134, (N, Kp // 32), dtype=np.uint8)
+    Yref = MX.gemm(ac, asc, wc, wsc)
+
+    def shifted(a, by):
+        buf = torch.zeros(a.size + 256, dtype=torch.uint8, device="cuda")
+        start = (-buf.data_ptr()) % 16 + by
+        view = buf[start:start + a.size].view(a.shape)
+        view.copy_(torch.from_numpy(a))
+        return view
+    Y = B.arcq_mx_gemm(shifted(ac, 4), shifted(asc, 3), shifted(wc, 12), shifted(wsc, 1), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    err = norm_err(Y.cpu().numpy(), Yref)
+    say(f"   normalised max error {err:.3e}")
+    assert err <= GEMM_TOL_F32
 
 
 def test_mx_gemm_extreme_scales():
