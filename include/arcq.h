@@ -243,10 +243,9 @@ arcq_status arcq_calib_select(const float* colmax, int64_t K, int32_t* perm, int
  * 16-byte aligned.  This is the block format gfx950's scaled FP4 matrix instruction multiplies natively,
  * so arcq_mx_gemm needs no decode:
  *   y[m, n] = sum_b 2^(sa[m,b]-127) 2^(sw[n,b]-127) sum_{i<32} qa[m,32b+i] qw[n,32b+i],  fp32 accumulation
- * (Section 3.2 eq. (2)); Kp % 32 == 0; codes 4-byte aligned.  Up to 64 rows (decode) every such shape runs on
- * the weight-streaming kernel; above that, 16-byte aligned codes, 4-byte aligned scales and Kp % 128 == 0
- * select the tiled kernels (about 5x faster than the fallback other shapes take: round S up to a multiple
- * of 128); y as in arcq_gemm.  No workspace (see arcq_mx_gemm_ws below).
+ * (Section 3.2 eq. (2)); Kp % 32 == 0; codes 4-byte aligned.  Every such shape runs on the tiled /
+ * weight-streaming kernels; 16-byte aligned codes, 4-byte aligned scales and Kp % 128 == 0 additionally let
+ * the tiled kernels copy straight into LDS (about 1.5x faster on large M); y as in arcq_gemm.  No workspace (see arcq_mx_gemm_ws below).
  */
 arcq_status arcq_mx_packed_sizes(int64_t rows, int64_t K, int64_t S,
                                  size_t* codes_bytes, size_t* scales_bytes);

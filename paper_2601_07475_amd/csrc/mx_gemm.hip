@@ -63,7 +63,15 @@ struct MxCfg {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-template <int WM, int WN, int GM, int GN, typename OutT, bool BF16 = false>
+//
+// REG: the same tiles, LDS layout and schedule for shapes the direct-to-LDS copies do not serve: any number of
+// blocks per row (K' a multiple of 32 only: rows of scale bytes then start at odd addresses) and operands at the
+// interface's minimum alignment.  A thread fetches its pieces of unit u+2 into registers with ordinary loads
+// (declared with the alignment the interface guarantees), all at once right after the barrier that opens unit u+1,
+// and writes them to LDS just before the barrier that opens their unit; blocks past the end of a row become zero
+// codes (a scale word that would reach past the end is fetched from further left and shifted), so every unit is a
+// whole unit.
+template <int WM, int WN, int GM, int GN, typename OutT, bool BF16 = false, bool REG = false>
 __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N, int nb,
@@ -93,8 +101,8 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
     const int wg_m0 = tile_m * C::BM, wg_n0 = tile_n * C::BN;
     const int wrow0 = (wave / GN) * (32 * WM), wcol0 = (wave % GN) * (32 * WN);
 
-    const bool has_half = (nb & 7) != 0;                    // nb % 8 == 4
-    const int nunit = (nb >> 3) + (has_half ? 1 : 0);
+    const bool has_half = !REG && (nb & 7) != 0;            // nb % 8 == 4
+    const int nunit = REG ? (nb + 7) >> 3 : (nb >> 3) + (has_half ? 1 : 0);
 
     // ---- copies: thread -> (row, piece) of a workgroup-wide copy; 8 lanes fetch one row's 128 bytes
     const uint32_t cpitch = (uint32_t)nb * 16u, spitch = (uint32_t)nb;
@@ -124,6 +132,47 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
             const int p = d - NA - NW - NAS;
             const uint32_t row = (uint32_t)min(wg_n0 + p * (NT / 2) + srow, N - 1);
             dma4(w_scales, row * spitch + os, base + C::W_SCALES + 4u * (p * NT + wave_slot));
+        }
+    };
+
+    // ---- REG: the same pieces through registers (piece d of a thread lands where copy d puts it); needs nb >= 4
+    constexpr int NCP = C::NA + C::NW, NSP = C::NAS + C::NWS;
+    uint4 rc[REG ? NCP : 1];
+    uint32_t rs[REG && NSP > 0 ? NSP : 1];
+    auto reg_issue = [&](int unit) {
+        const uint32_t oc = 16u * (uint32_t)min(8 * unit + (int)lp, nb - 1);
+#pragma unroll
+        for (int d = 0; d < NCP; ++d) {
+            const bool is_a = d < C::NA;
+            const int p = is_a ? d : d - C::NA;
+            const uint32_t row = (uint32_t)(is_a ? min(wg_m0 + p * (C::NT / 8) + crow, M - 1) : min(wg_n0 + p * (C::NT / 8) + crow, N - 1));
+            rc[d] = load16_a4((is_a ? a_codes : w_codes) + (size_t)(row * cpitch + oc));
+        }
+        const uint32_t os = (uint32_t)min(8 * unit + 4 * (tid & 1), nb - 4);
+#pragma unroll
+        for (int d = 0; d < NSP; ++d) {
+            const bool is_a = d < C::NAS;
+            const int p = is_a ? d : d - C::NAS;
+            const uint32_t row = (uint32_t)(is_a ? min(wg_m0 + p * (C::NT / 2) + srow, M - 1) : min(wg_n0 + p * (C::NT / 2) + srow, N - 1));
+            rs[d] = load4_a1((is_a ? a_scales : w_scales) + (size_t)(row * spitch + os));
+        }
+    };
+    auto reg_commit = [&](int unit, int buf) {
+        uint8_t* st = lds + buf * C::UNIT_BYTES;
+        const bool ok = 8 * unit + (int)lp < nb;       // this piece's block exists
+#pragma unroll
+        for (int d = 0; d < NCP; ++d) {
+            const uint4 v = uint4{ok ? rc[d].x : 0u, ok ? rc[d].y : 0u, ok ? rc[d].z : 0u, ok ? rc[d].w : 0u};
+            const int at = d < C::NA ? C::A_CODES + 16 * (d * C::NT + tid) : C::W_CODES + 16 * ((d - C::NA) * C::NT + tid);
+            *reinterpret_cast<uint4*>(st + at) = v;
+        }
+        const int sb0 = 8 * unit + 4 * (tid & 1);       // this word: blocks sb0 .. sb0 + 3
+        const int skip = sb0 - min(sb0, nb - 4);        // bytes of the fetched word that belong to earlier blocks
+#pragma unroll
+        for (int d = 0; d < NSP; ++d) {
+            const uint32_t word = skip >= 4 ? 0u : rs[d] >> (8 * skip);
+            const int at = d < C::NAS ? C::A_SCALES + 4 * (d * C::NT + tid) : C::W_SCALES + 4 * ((d - C::NAS) * C::NT + tid);
+            *reinterpret_cast<uint32_t*>(st + at) = word;
         }
     };
 
@@ -179,6 +228,7 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
     auto run_unit = [&](int u, auto nsteps_tag) {
         constexpr int NSTEPS = decltype(nsteps_tag)::value;
         constexpr int LAST_Q = NSTEPS * NM - NM / 2;
+        constexpr int COMMIT_Q = LAST_Q - NM / 2;     // REG: the pieces of unit u+1 go to LDS half a k-step before its barrier
         const uint8_t* st = lds + buf * C::UNIT_BYTES;
         const int buf1 = buf + 1 == C::NUNIT ? 0 : buf + 1, bufd = buf == 0 ? C::NUNIT - 1 : buf - 1;
         const int fetch = min(u + DIST, nunit - 1);
@@ -193,12 +243,19 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
 #pragma unroll
                 for (int j = 0; j < WN; ++j) {
                     const int q = t * NM + i * WN + j;
+                    if (REG && q == COMMIT_Q) {
+                        reg_commit(min(u + 1, nunit - 1), buf1);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                     if (q == LAST_Q) {
                         // unit u+1 must have landed: the copies of the DIST - 1 later units are younger
-                        wait_vmcnt<(DIST - 1) * C::NDMA>();
+                        // (REG: this wave's LDS writes of unit u+1 must have completed)
+                        if constexpr (REG) wait_lgkmcnt0();
+                        else wait_vmcnt<(DIST - 1) * C::NDMA>();
                         wg_barrier();
                         read_codes(0, 0, lds + buf1 * C::UNIT_BYTES);
                         read_scales(lds + buf1 * C::UNIT_BYTES, sa_n, sw_n);
+                        if constexpr (REG) reg_issue(min(u + 2, nunit - 1));
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     // weights as the row operand: see store_tile_swapped
@@ -209,7 +266,7 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
                         acc[i][j] = mfma_mx(fw[t & 1][j], fa[t & 1][i], acc[i][j], (int)(t < 2 ? sw[j].x : sw[j].y),
                                             (int)(t < 2 ? sa[i].x : sa[i].y), t & 1);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (NSTEPS == 4 && q < C::NDMA) {
+                    if (!REG && NSTEPS == 4 && q < C::NDMA) {
                         issue_one(q, fetch, bufd);
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -227,15 +284,22 @@ __global__ __launch_bounds__(64 * GM * GN) void mx_gemm_staged_kernel(
 
     // this workgroup's run of units [u0, u1); copies past the run fetch units the run never uses (in bounds)
     const int u0 = (int)((int64_t)split * nunit / splits), u1 = (int)((int64_t)(split + 1) * nunit / splits);
+    if constexpr (REG) {
+        reg_issue(u0);
+        reg_commit(u0, 0);
+        reg_issue(min(u0 + 1, nunit - 1));
+        wait_lgkmcnt0();
+    } else {
 #pragma unroll
-    for (int u = 0; u < DIST; ++u)
+        for (int u = 0; u < DIST; ++u)
 #pragma unroll
-        for (int d = 0; d < C::NDMA; ++d) issue_one(d, min(u0 + u, nunit - 1), u);
-    wait_vmcnt<(DIST - 1) * C::NDMA>();
+            for (int d = 0; d < C::NDMA; ++d) issue_one(d, min(u0 + u, nunit - 1), u);
+        wait_vmcnt<(DIST - 1) * C::NDMA>();
+    }
     wg_barrier();
     read_codes(0, 0, lds);
     read_scales(lds, sa, sw);
-    const int nfull = nb >> 3;
+    const int nfull = REG ? nunit : nb >> 3;
     for (int u = u0; u < min(u1, nfull); ++u) run_unit(u, std::integral_constant<int, 4>{});
     if (has_half && u1 == nunit) run_unit(nfull, std::integral_constant<int, 2>{});
     wait_vmcnt<0>();                            // no copy may still be in flight when the LDS is released
@@ -469,7 +533,7 @@ arcq_status launch_mx_skinny(const uint8_t* a_codes, const uint8_t* a_scales, co
     return check_launch("mx_gemm_skinny_kernel");
 }
 
-template <int WM, int WN, int GM, int GN, typename OutT, bool BF16 = false>
+template <int WM, int WN, int GM, int GN, typename OutT, bool BF16 = false, bool REG = false>
 arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                              const uint8_t* w_scales, int M, int N, int nb, OutT* y, int64_t ldy, hipStream_t stream,
                              int splits = 1, float* partial = nullptr) {
@@ -477,7 +541,7 @@ arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, co
     const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
     if (splits > 1) {
         // fp32 partial results [splits, M, N] in the workspace, then one pass that adds them
-        auto kern = mx_gemm_staged_kernel<WM, WN, GM, GN, float, BF16>;
+        auto kern = mx_gemm_staged_kernel<WM, WN, GM, GN, float, BF16, REG>;
         static std::atomic<uint64_t> lds_raised{0};
         if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
         hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n * splits), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales,
@@ -486,7 +550,7 @@ arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, co
         return launch_splitk_reduce(partial, splits, M, N, 1.0f, y, std::is_same<OutT, _Float16>::value ? ARCQ_DTYPE_F16 : ARCQ_DTYPE_F32,
                                     ldy, stream);
     }
-    auto kern = mx_gemm_staged_kernel<WM, WN, GM, GN, OutT, BF16>;
+    auto kern = mx_gemm_staged_kernel<WM, WN, GM, GN, OutT, BF16, REG>;
     static std::atomic<uint64_t> lds_raised{0};
     if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(C::NT), C::LDS_BYTES, stream, a_codes, a_scales, w_codes,
@@ -502,7 +566,7 @@ arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, co
 int mx_split_k(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nb = Kp >> 5;
     const bool streaming = M <= 32 ? N * Kp < 200000000 : M <= 64 && N < 8192;
-    if (streaming || (nb & 3) != 0) return 1;
+    if (streaming || nb < 8) return 1;
     if (((M + 255) / 256) * ((N + 255) / 256) >= 256 || ((M + 127) / 128) * ((N + 255) / 256) >= 192) return 1;
     const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
     const int64_t nunit = (nb + 7) >> 3;
@@ -560,6 +624,17 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
             return launch_mx_staged<2, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
         return launch_mx_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream,
                                             workspace ? mx_split_k(M, N, Kp) : 1, workspace);
+    }
+    if (nb >= 8 && offsets_fit) {
+        // any K' that is a multiple of 32, operands at their minimum alignment: units through registers
+        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+        if (t256 >= 256)
+            return launch_mx_staged<4, 4, 2, 2, OutT, false, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
+        const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
+        if (t128x256 >= 192)
+            return launch_mx_staged<2, 4, 2, 2, OutT, false, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
+        return launch_mx_staged<2, 2, 2, 2, OutT, false, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream,
+                                                               workspace ? mx_split_k(M, N, Kp) : 1, workspace);
     }
     dim3 grid((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128));
     hipLaunchKernelGGL(mx_gemm_direct_kernel<OutT>, grid, dim3(256), 0, stream, a_codes, a_scales, w_codes, w_scales,

@@ -634,6 +634,10 @@ MX_GEMM_SHAPES = [  # M, N, K, S: fallback kernel (K' % 128 != 0), every staged 
     # weight-streaming kernel with K' % 128 != 0: a last chunk of 1, 2 or 3 blocks, rows shorter than a chunk
     (8, 40, 96, 0), (3, 17, 32, 32), (20, 300, 512, 160), (33, 77, 2048, 2016), (64, 4097, 256, 96), (1, 4096, 14336, 288),
     (17, 14336, 512, 480),
+    # the same on the tiled kernels, units through registers: 128 x 128 tiles without and with split K' (the last unit
+    # holds 1, 7 and 5 blocks), 128 x 256 and 256 x 256 tiles
+    (257, 131, 1024, 32), (300, 77, 2048, 2016), (500, 260, 4096, 160), (1990, 4070, 256, 96), (4000, 4100, 288, 32),
+    (96, 9000, 992, 96),
 ]
 
 
@@ -652,7 +656,7 @@ def test_mx_gemm_parity(M, N, K, S, dtype):
     assert err <= (GEMM_TOL_F16 if dtype == torch.float16 else GEMM_TOL_F32)
 
 
-@pytest.mark.parametrize("M,N,Kp", [(16, 1000, 1024), (64, 300, 4384)])
+@pytest.mark.parametrize("M,N,Kp", [(16, 1000, 1024), (64, 300, 4384), (300, 260, 1024), (2048, 3000, 256)])
 def test_mx_gemm_operands_only_4_byte_aligned(M, N, Kp):
     """Codes 4 bytes off a 16-byte boundary and scale bytes at odd addresses: the least the interface asks for."""
     say(f"mx_gemm with 4-byte aligned operands M={M} N={N} K'={Kp}")
