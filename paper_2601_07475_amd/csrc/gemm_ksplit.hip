@@ -12,7 +12,7 @@
 // pieces of a row are XOR-swizzled so that 16 consecutive rows fall on 16 different bank groups (rows are 128
 // bytes apart for KS = 4: swizzle (row >> 1) & 7; 64 bytes for KS = 2: (row >> 2) & 3).
 // At the end the KS partial tiles are added through the LDS in KS - 1 rounds; fragment f of a sub-tile is owned
-// (finished and stored) by wave kh = f % KS.
+// (finished and stored) by wave kh = f % KS (with six fragments and four waves two waves own two, two own one).
 #include "internal.h"
 #include "gemm_decode.h"
 #include "gemm_epilogue.h"
@@ -27,7 +27,6 @@ namespace {
 template <int WM, int WN, int GM, int GN, int KS>
 struct KsplitCfg {
     static_assert(KS == 2 || KS == 4, "k halves or quarters");
-    static_assert((WM * WN) % KS == 0, "every wave owns the same number of fragments");
     static constexpr int BM = 32 * WM * GM, BN = 32 * WN * GN;
     static constexpr int NWAVE = GM * GN * KS, NT = 64 * NWAVE;
     static constexpr int ROWB = 32 * KS;            // code bytes of a row per stage
@@ -44,7 +43,7 @@ struct KsplitCfg {
     static constexpr int W_SCALES = A_SCALES + NAS * NT * 4;
     static constexpr int STAGE_BYTES = W_SCALES + NWS * NT * 4;
     static constexpr int NSTAGE = 3, DIST = 2;
-    static constexpr int OWN = WM * WN / KS;         // fragments a wave finishes and stores
+    static constexpr int OWN = (WM * WN + KS - 1) / KS;  // fragments a wave finishes and stores (at most)
     static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
     static_assert(NWAVE * OWN * 4096 <= LDS_BYTES, "the exchange regions must fit the operand ring");
     static_assert((NT / PPR) % 16 == 0 && (NT / KS) % 1 == 0, "row swizzle must not depend on the copy index");
@@ -304,13 +303,14 @@ arcq_status launch_ksplit_typed(int variant, const uint8_t* a_codes, const uint8
     switch (variant) {
         case 1: return launch_ksplit<2, 2, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 64 x 64
         case 2: return launch_ksplit<4, 2, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 128 x 64
+        case 4: return launch_ksplit<3, 2, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 96 x 64
         default: return launch_ksplit<2, 4, 2, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);  // 128 x 128
     }
 }
 
 }  // namespace
 
-// 0: not served here; 1: 64 x 64 tiles; 2: 128 x 64 tiles; 3: 128 x 128 tiles (k quarters inside the workgroup each)
+// 0: not served here; 1: 64 x 64 tiles; 4: 96 x 64; 2: 128 x 64 tiles; 3: 128 x 128 tiles (k quarters inside the workgroup each)
 int gemm_ksplit_variant(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nbk = Kp >> 4;
     if ((nbk & 15) != 0 || nbk < 32) return 0;            // whole stages of 256 k, at least two
@@ -323,9 +323,10 @@ int gemm_ksplit_variant(int64_t M, int64_t N, int64_t Kp) {
     // 1024: against the 128 x 128 tiles with K' split across workgroups these run 64 x 64 tiles 1.2-1.8x, 128 x 64
     // tiles 1.1-1.5x and 128 x 128 tiles 1.05-1.2x faster; with fewer tiles the split across workgroups wins, with
     // more the larger tiles of gemm.hip do).
-    const int64_t m64 = (M + 63) / 64, m128 = (M + 127) / 128, n64 = (N + 63) / 64, n128 = (N + 127) / 128;
+    const int64_t m64 = (M + 63) / 64, m96 = (M + 95) / 96, m128 = (M + 127) / 128, n64 = (N + 63) / 64, n128 = (N + 127) / 128;
     auto fits = [](int64_t tiles) { return tiles >= 144 && tiles <= 256; };
     if (fits(m64 * n64)) return 1;
+    if (fits(m96 * n64)) return 4;
     if (fits(m128 * n64)) return 2;
     if (fits(m128 * n128)) return 3;
     return 0;
