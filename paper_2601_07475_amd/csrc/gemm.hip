@@ -1085,11 +1085,22 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
             return launch_gemm_ksplit(variant, a_codes, a_scales, w_codes, w_scales, M, N, Kp, alpha, y,
                                       std::is_same<OutT, _Float16>::value ? ARCQ_DTYPE_F16 : ARCQ_DTYPE_F32, ldy, stream);
     if ((nbk & 3) == 0 && nbk >= 8 && offsets_fit && aligned16) {
-        // big tiles when they still give every CU work; otherwise smaller ones
-        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-        if (t256 >= 256)
-            return launch_staged<4, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
-        const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
+        // Tiles of 256 weight rows by 256, 192 or 128 activation rows when there is work for them.  Workgroups run in
+        // rounds of one per compute unit and a round lasts as long as one tile, so the tile height that minimises
+        // rounds x (time of a stage of that tile) wins: 2.96, 2.59 and 1.96 us measured per 128-k stage (the bigger
+        // tile decodes fewer fragments per matrix instruction: 45, 53 and 60 ps per output element and stage).
+        // E.g. 768 x 14336: 224 tiles of 192 rows in one round 88 us, 336 tiles of 128 rows in two rounds 113 us,
+        // 168 tiles of 256 rows 100 us; 1024 x 14336: 224 tiles of 256 rows 106 us against 120 us.
+        const int64_t tn256 = (N + 255) / 256;
+        const int64_t t128x256 = ((M + 127) / 128) * tn256;
+        if (t128x256 >= 192) {
+            auto cost = [&](int bm, double t_stage) { return (double)((((M + bm - 1) / bm) * tn256 + 255) / 256) * t_stage; };
+            const double c256 = cost(256, 2.96), c192 = cost(192, 2.59), c128 = cost(128, 1.96);
+            if (c256 <= c192 && c256 <= c128)
+                return launch_staged<4, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+            if (c192 <= c128)
+                return launch_staged<3, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+        }
         // 128 x 256 tiles with 8 waves of 64 x 64 (two per SIMD): 5 % faster than 4 waves of 64 x 128 on the
         // 2048 x 4096 x 4352 problem; on the large shapes 4 and 8 waves measure the same
         if (t128x256 >= 192) {

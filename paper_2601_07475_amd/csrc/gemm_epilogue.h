@@ -118,8 +118,10 @@ template <int WM, int WN>
 __device__ __forceinline__ void store_tile_f16_via_lds(const float16v (&acc)[WM][WN], uint8_t* lds_wave, int m0, int n0,
                                                        int lane, int M, int N, float alpha, _Float16* __restrict__ y,
                                                        int64_t ldy, bool vec_ok) {
-    static_assert(WM == 2 || WM == 4, "two fragment rows at a time");
+    static_assert(WM >= 2 && WM <= 4, "two fragment rows at a time, then the rest");
     store_fragment_rows_f16_via_lds<WM, WN, 0, 2>(acc, lds_wave, m0, n0, lane, M, N, alpha, y, ldy, vec_ok);
+    if constexpr (WM == 3)
+        store_fragment_rows_f16_via_lds<WM, WN, 2, 1>(acc, lds_wave, m0, n0, lane, M, N, alpha, y, ldy, vec_ok);
     if constexpr (WM == 4)
         store_fragment_rows_f16_via_lds<WM, WN, 2, 2>(acc, lds_wave, m0, n0, lane, M, N, alpha, y, ldy, vec_ok);
 }

@@ -289,6 +289,9 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     (130, 3100, 512, 0), (192, 4096, 4096, 256), (300, 3500, 1024, 256), (700, 3900, 448, 64), (1024, 4096, 1024, 256),
     # ... 96 x 64 tiles (six fragments over four waves: two waves finish two, two finish one), exact and ragged; 128 x 64
     (384, 4096, 1024, 0), (290, 3500, 512, 256), (512, 4000, 512, 0),
+    # 192 x 256 tiles (one round of them where 128-row tiles need two): ragged edges, whole stages and a half stage at the end;
+    # 256 x 256 tiles that fill only part of the chip (fewer than 256 of them)
+    (570, 14000, 192, 64), (1100, 8000, 256, 64), (1000, 14100, 128, 64),
     # K' with an odd number of blocks, or K' % 64 = 32 (S is any multiple of 16): rows that start 8 bytes off a 16-byte
     # boundary.  Weight-streaming kernel with 1, 2, 4 and 8 row tiles, one block per row, last chunk of 1, 3, 5, 7 blocks
     (8, 40, 16, 0), (1, 300, 1008, 0), (16, 1000, 4096, 272), (16, 4097, 1008, 48), (33, 77, 2048, 2000), (20, 300, 512, 48),
