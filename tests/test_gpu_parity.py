@@ -763,7 +763,8 @@ def test_ref_gemm_bf16_against_fp64(M, N, K):
     assert norm_err(Y, Yref) <= GEMM_TOL_F16
 
 
-@pytest.mark.parametrize("M,N,K,S", [(200, 260, 8192, 512), (130, 129, 4192, 32), (384, 1000, 6144, 0), (100, 300, 14336, 256)])
+@pytest.mark.parametrize("M,N,K,S", [(200, 260, 8192, 512), (130, 129, 4192, 32), (384, 1000, 6144, 0), (100, 300, 14336, 256),
+                                     (200, 260, 8192, 544)])      # the last: an odd number of blocks, units through registers
 @pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
 def test_mx_gemm_with_workspace_splits_the_reduction(M, N, K, S, dtype):
     """Few-tile problems with a long K' on arcq_mx_gemm_ws: 2 to 8 runs (the second ends with a half unit), against the
