@@ -1050,7 +1050,15 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
                          const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, float alpha, OutT* y,
                          int64_t ldy, float* workspace, hipStream_t stream) {
     const int nbk = (int)(Kp >> 4);
-    if (skinny_shape(M, N, Kp)) {
+    const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
+                           ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 3) == 0;
+    // 33 to 64 rows against many weight rows: 64 x 64 tiles with the k split inside the workgroup decode every activation
+    // fragment once per tile, the weight-streaming kernel once per 32 weight rows
+    // (measured with weights from HBM, 64 rows: 14336 x 4352 15.8 us against 21.8, 9216 x 4352 15.3 against 25.3,
+    // 12288 x 8448 25.0 against 44.8; 33 rows gain as long as the tiles are 64 x 64)
+    const int ks_variant = M > 32 && aligned16 ? gemm_ksplit_variant(M, N, Kp) : 0;
+    const bool tiles_instead = ks_variant == 1 || (ks_variant != 0 && M > 48);
+    if (skinny_shape(M, N, Kp) && !tiles_instead) {
         // Weight-streaming path.  Enough waves to keep the weight stream in flight, as few as that allows
         // so that each wave has several KB to request at once: with many weight rows several tiles per
         // wave share the activation operand; with few, one tile per wave so that every CU still gets a
@@ -1078,8 +1086,6 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
 #undef ARCQ_SKINNY_W
     }
     const bool offsets_fit = (uint64_t)M * (uint64_t)nbk * 8 < 0xFFFF0000ull && (uint64_t)N * (uint64_t)nbk * 8 < 0xFFFF0000ull;
-    const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
-                           ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 3) == 0;
     if (aligned16)
         if (const int variant = gemm_ksplit_variant(M, N, Kp))
             return launch_gemm_ksplit(variant, a_codes, a_scales, w_codes, w_scales, M, N, Kp, alpha, y,

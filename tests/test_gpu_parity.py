@@ -289,6 +289,8 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     (130, 3100, 512, 0), (192, 4096, 4096, 256), (300, 3500, 1024, 256), (700, 3900, 448, 64), (1024, 4096, 1024, 256),
     # ... 96 x 64 tiles (six fragments over four waves: two waves finish two, two finish one), exact and ragged; 128 x 64
     (384, 4096, 1024, 0), (290, 3500, 512, 256), (512, 4000, 512, 0),
+    # 33 to 64 rows against many weight rows: the 64 x 64 k-split tiles instead of the weight-streaming kernel
+    (50, 9300, 512, 0), (64, 14336, 256, 256), (33, 9216, 1024, 0),
     # 192 x 256 tiles (one round of them where 128-row tiles need two): ragged edges, whole stages and a half stage at the end;
     # 256 x 256 tiles that fill only part of the chip (fewer than 256 of them)
     (570, 14000, 192, 64), (1100, 8000, 256, 64), (1000, 14100, 128, 64),
