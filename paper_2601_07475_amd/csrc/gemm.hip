@@ -1057,7 +1057,7 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
     // (measured with weights from HBM, 64 rows: 14336 x 4352 15.8 us against 21.8, 9216 x 4352 15.3 against 25.3,
     // 12288 x 8448 25.0 against 44.8; 33 rows gain as long as the tiles are 64 x 64)
     const int ks_variant = M > 32 && aligned16 ? gemm_ksplit_variant(M, N, Kp) : 0;
-    const bool tiles_instead = ks_variant == 1 || (ks_variant != 0 && M > 48);
+    const bool tiles_instead = ks_variant == 1 || ks_variant == 6 || (ks_variant != 0 && M > 48);
     if (skinny_shape(M, N, Kp) && !tiles_instead) {
         // Weight-streaming path.  Enough waves to keep the weight stream in flight, as few as that allows
         // so that each wave has several KB to request at once: with many weight rows several tiles per

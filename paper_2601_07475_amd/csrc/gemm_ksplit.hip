@@ -304,13 +304,14 @@ arcq_status launch_ksplit_typed(int variant, const uint8_t* a_codes, const uint8
         case 1: return launch_ksplit<2, 2, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 64 x 64
         case 2: return launch_ksplit<4, 2, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 128 x 64
         case 4: return launch_ksplit<3, 2, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 96 x 64
+        case 6: return launch_ksplit<2, 1, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 64 x 32
         default: return launch_ksplit<2, 4, 2, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);  // 128 x 128
     }
 }
 
 }  // namespace
 
-// 0: not served here; 1: 64 x 64 tiles; 4: 96 x 64; 2: 128 x 64 tiles; 3: 128 x 128 tiles (k quarters inside the workgroup each)
+// 0: not served here; 6: 64 x 32 tiles; 1: 64 x 64; 4: 96 x 64; 2: 128 x 64; 3: 128 x 128 (k quarters inside the workgroup each)
 int gemm_ksplit_variant(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nbk = Kp >> 4;
     if ((nbk & 15) != 0 || nbk < 32) return 0;            // whole stages of 256 k, at least two
@@ -325,6 +326,7 @@ int gemm_ksplit_variant(int64_t M, int64_t N, int64_t Kp) {
     // more the larger tiles of gemm.hip do).
     const int64_t m64 = (M + 63) / 64, m96 = (M + 95) / 96, m128 = (M + 127) / 128, n64 = (N + 63) / 64, n128 = (N + 127) / 128;
     auto fits = [](int64_t tiles) { return tiles >= 144 && tiles <= 256; };
+    if (fits(m64 * ((N + 31) / 32))) return 6;
     if (fits(m64 * n64)) return 1;
     if (fits(m96 * n64)) return 4;
     if (fits(m128 * n64)) return 2;

@@ -291,6 +291,8 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     (384, 4096, 1024, 0), (290, 3500, 512, 256), (512, 4000, 512, 0),
     # 33 to 64 rows against many weight rows: the 64 x 64 k-split tiles instead of the weight-streaming kernel
     (50, 9300, 512, 0), (64, 14336, 256, 256), (33, 9216, 1024, 0),
+    # 64 x 32 tiles (two fragments over four k-quarter waves: two of the waves finish none)
+    (64, 6100, 512, 0), (100, 4000, 768, 256), (40, 5000, 4096, 256),
     # 192 x 256 tiles (one round of them where 128-row tiles need two): ragged edges, whole stages and a half stage at the end;
     # 256 x 256 tiles that fill only part of the chip (fewer than 256 of them)
     (570, 14000, 192, 64), (1100, 8000, 256, 64), (1000, 14100, 128, 64),
