@@ -289,6 +289,9 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     (130, 3100, 512, 0), (192, 4096, 4096, 256), (300, 3500, 1024, 256), (700, 3900, 448, 64), (1024, 4096, 1024, 256),
     # ... 96 x 64 tiles (six fragments over four waves: two waves finish two, two finish one), exact and ragged; 128 x 64
     (384, 4096, 1024, 0), (290, 3500, 512, 256), (512, 4000, 512, 0),
+    # three weight tiles per wave on the weight-streaming kernel (513 to 768 tiles of 16 weight rows), 16 and 32 rows
+    (16, 10240, 512, 32), (9, 8300, 1040, 16), (32, 9000, 256, 64), (20, 12288, 4096, 256), (32, 7000, 512, 0),
+    (32, 12400, 528, 0),
     # 33 to 64 rows against many weight rows: the 64 x 64 k-split tiles instead of the weight-streaming kernel
     (50, 9300, 512, 0), (64, 14336, 256, 256), (33, 9216, 1024, 0),
     # 64 x 32 tiles (two fragments over four k-quarter waves: two of the waves finish none)
