@@ -646,6 +646,8 @@ MX_GEMM_SHAPES = [  # M, N, K, S: fallback kernel (K' % 128 != 0), every staged 
     # weight-streaming kernel with K' % 128 != 0: a last chunk of 1, 2 or 3 blocks, rows shorter than a chunk
     (8, 40, 96, 0), (3, 17, 32, 32), (20, 300, 512, 160), (33, 77, 2048, 2016), (64, 4097, 256, 96), (1, 4096, 14336, 288),
     (17, 14336, 512, 480),
+    # three and four weight tiles per wave on the weight-streaming kernel
+    (16, 10240, 512, 0), (32, 9000, 256, 64), (32, 12400, 512, 32),
     # the same on the tiled kernels, units through registers: 128 x 128 tiles without and with split K' (the last unit
     # holds 1, 7 and 5 blocks), 128 x 256 and 256 x 256 tiles
     (257, 131, 1024, 32), (300, 77, 2048, 2016), (500, 260, 4096, 160), (1990, 4070, 256, 96), (4000, 4100, 288, 32),
