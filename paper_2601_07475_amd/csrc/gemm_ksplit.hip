@@ -326,7 +326,11 @@ int gemm_ksplit_variant(int64_t M, int64_t N, int64_t Kp) {
     // more the larger tiles of gemm.hip do).
     const int64_t m64 = (M + 63) / 64, m96 = (M + 95) / 96, m128 = (M + 127) / 128, n64 = (N + 63) / 64, n128 = (N + 127) / 128;
     auto fits = [](int64_t tiles) { return tiles >= 144 && tiles <= 256; };
-    if (fits(m64 * ((N + 31) / 32))) return 6;
+    // the smallest tile also with fewer workgroups, for more than 64 rows and a short reduction (a tile takes 10.7 us
+    // over K' = 4352, 17.3 over 8448, 27 over 14592 whatever their number; the alternatives, the eight-row-tile
+    // streaming kernel and 128 x 128 tiles with K' split across workgroups, take 15-17, 21-29 and 24-26 us there)
+    const int64_t t6 = m64 * ((N + 31) / 32);
+    if (fits(t6) || (M > 64 && nbk <= 544 && t6 >= 32 && t6 <= 256)) return 6;
     if (fits(m64 * n64)) return 1;
     if (fits(m96 * n64)) return 4;
     if (fits(m128 * n64)) return 2;

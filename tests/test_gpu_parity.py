@@ -275,7 +275,7 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     (128, 45, 160, 32), (17, 14336, 512, 512), (48, 2048, 4096, 1024),
     # more than 128 rows but few tiles: the reduction dimension is split into 2 to 8 runs (the last run of the third
     # ends with a half stage) and the partial results are added by a second kernel; the fourth is too short to split
-    (256, 512, 4096, 256), (300, 260, 4160, 64), (130, 129, 2048, 64), (200, 140, 576, 64), (384, 1000, 1024, 64),
+    (256, 512, 14336, 256), (300, 260, 4160, 64), (130, 129, 2048, 64), (200, 140, 576, 64), (384, 1000, 1024, 64),
     # ragged edges in every tile configuration of the staged kernel: 128 x 256 tiles (8 waves), 256 x 256 tiles
     (1990, 4070, 256, 64), (4000, 4100, 128, 64),
     # the same 128 x 256 tiles with K' a multiple of 128: the kernel whose wave pairs split every stage
@@ -295,7 +295,7 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     # 33 to 64 rows against many weight rows: the 64 x 64 k-split tiles instead of the weight-streaming kernel
     (50, 9300, 512, 0), (64, 14336, 256, 256), (33, 9216, 1024, 0),
     # 64 x 32 tiles (two fragments over four k-quarter waves: two of the waves finish none)
-    (64, 6100, 512, 0), (100, 4000, 768, 256), (40, 5000, 4096, 256),
+    (64, 6100, 512, 0), (100, 4000, 768, 256), (40, 5000, 4096, 256), (128, 500, 512, 0), (200, 1000, 4096, 256),
     # 192 x 256 tiles (one round of them where 128-row tiles need two): ragged edges, whole stages and a half stage at the end;
     # 256 x 256 tiles that fill only part of the chip (fewer than 256 of them)
     (570, 14000, 192, 64), (1100, 8000, 256, 64), (1000, 14100, 128, 64),

@@ -113,11 +113,11 @@ def test_gemm_argument_errors():
     assert B.lib().arcq_gemm_workspace_size(4, 8, 64, ctypes.byref(n)) == B.OK
     assert B.lib().arcq_gemm_workspace_size(4, 8, 40, ctypes.byref(n)) == B.BAD_SHAPE
     # few tiles and a long reduction: split into several runs (at most 8), fp32 partial results in the workspace
-    assert B.lib().arcq_gemm_workspace_size(256, 512, 4352, ctypes.byref(n)) == B.OK
+    assert B.lib().arcq_gemm_workspace_size(256, 512, 14592, ctypes.byref(n)) == B.OK
     assert n.value % (256 * 512 * 4) == 0 and 2 <= n.value // (256 * 512 * 4) <= 8
-    assert g(M=256, N=512, Kp=4352, ldy=512) == B.WORKSPACE_TOO_SMALL
-    assert g(M=256, N=512, Kp=4352, ldy=512, ws=FAKE, wsb=1024) == B.WORKSPACE_TOO_SMALL
-    assert g(M=256, N=512, Kp=4352, ldy=512, ws=ctypes.c_void_p(0x10010), wsb=1 << 30) == B.BAD_ALIGN
+    assert g(M=256, N=512, Kp=14592, ldy=512) == B.WORKSPACE_TOO_SMALL
+    assert g(M=256, N=512, Kp=14592, ldy=512, ws=FAKE, wsb=1024) == B.WORKSPACE_TOO_SMALL
+    assert g(M=256, N=512, Kp=14592, ldy=512, ws=ctypes.c_void_p(0x10010), wsb=1 << 30) == B.BAD_ALIGN
     assert B.lib().arcq_gemm_workspace_size(2048, 4096, 4352, ctypes.byref(n)) == B.OK and n.value == 0
 
 
