@@ -563,9 +563,21 @@ arcq_status launch_mx_staged(const uint8_t* a_codes, const uint8_t* a_scales, co
 // microseconds, is rounds of workgroups over the 256 CUs times the units of a run at about 0.65 us a unit, plus,
 // when split, the write and read of the fp32 partial results at about 3 TB/s and 5.5 us for the shorter runs'
 // pipeline fill and the second launch (fitted to measurements over N = 2048 .. 8192, K' = 4352 .. 29696).
+// Shapes the weight-streaming kernel serves: up to 64 rows while the tiled kernels (with K' split across workgroups
+// where tiles are few) are not faster already.  Measured over N = 1024 .. 28672, K' = 4352 .. 28928: up to 16 rows
+// below 2 * 10^8 weights (10^8 when K' >= 16384: 5120 x 27904 27.5 us streamed, 19 us tiled); 17 to 32 rows below
+// 1.2 * 10^8 (5120 x 27904: 40 us streamed, 19 us tiled); 33 to 64
+// rows below 2.2 * 10^7 and fewer than 8192 weight rows (6144 x 4352: 13.2 against 11.2 us).  On the FP4 instruction a 128- or 256-row tile costs no
+// more than a 16-row one, so the tiled kernels win as soon as their tiles fill the chip.
+static bool mx_streaming_shape(int64_t M, int64_t N, int64_t Kp) {
+    const int64_t weights = N * Kp;
+    if (M <= 16) return weights < 200000000 && !(Kp >= 16384 && weights >= 100000000);
+    return M <= 32 ? weights < 120000000 : M <= 64 && N < 8192 && weights < 22000000;
+}
+
 int mx_split_k(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nb = Kp >> 5;
-    const bool streaming = M <= 32 ? N * Kp < 200000000 : M <= 64 && N < 8192;
+    const bool streaming = mx_streaming_shape(M, N, Kp);
     if (streaming || nb < 8) return 1;
     if (((M + 255) / 256) * ((N + 255) / 256) >= 256 || ((M + 127) / 128) * ((N + 255) / 256) >= 192) return 1;
     const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
@@ -593,11 +605,7 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
     const bool offsets_fit = (uint64_t)M * (uint64_t)nb * 16 < 0xFFFF0000ull && (uint64_t)N * (uint64_t)nb * 16 < 0xFFFF0000ull;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
                            ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 3) == 0;
-    // The weight-streaming kernel up to 64 rows, unless the tiled kernels are faster already: from 33 rows on
-    // with many weight rows, for any M with more than 2 * 10^8 weights (measured over N = 1024 .. 28672,
-    // K' = 2176 .. 14592, M = 16 .. 128: on the FP4 instruction a 128- or 256-row tile costs no more than a
-    // 16-row one, so the tiled kernels win as soon as their tiles fill the chip; above 64 rows they always did).
-    const bool streaming = M <= 32 ? N * Kp < 200000000 : M <= 64 && N < 8192;
+    const bool streaming = mx_streaming_shape(M, N, Kp);
     if (streaming) {
         const int64_t tiles = (N + 15) / 16;
 #define ARCQ_MX_SKINNY(MT_, NT_, W_, U_) \
@@ -621,23 +629,32 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
         ARCQ_MX_SKINNY(4, 1, 8, 1);
 #undef ARCQ_MX_SKINNY
     }
+    // Tiles of 256 weight rows by 256, 192 or 128 activation rows when there is work for them: workgroups run in rounds
+    // of one per compute unit, a round lasts as long as one tile, and a tile's time follows the bytes it copies per
+    // unit, 136 (rows of A + rows of W): the height that minimises rounds x (height + 256) wins (e.g. 1024 x 10240:
+    // 240 tiles of 192 rows in one round instead of 320 of 128 rows in two).
+    const int64_t tn256 = (N + 255) / 256, t128x256 = ((M + 127) / 128) * tn256;
+    auto tile_cost = [&](int64_t bm) { return ((((M + bm - 1) / bm) * tn256 + 255) / 256) * (bm + 256); };
+    const int tile_rows = t128x256 < 192 ? 0
+                          : tile_cost(256) <= tile_cost(192) && tile_cost(256) <= tile_cost(128) ? 256
+                          : tile_cost(192) <= tile_cost(128) ? 192 : 128;
     if ((nb & 3) == 0 && offsets_fit && aligned16) {
-        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-        if (t256 >= 256)
+        if (tile_rows == 256)
             return launch_mx_staged<4, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
-        const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
-        if (t128x256 >= 192)
+        if (tile_rows == 192)
+            return launch_mx_staged<3, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
+        if (tile_rows == 128)
             return launch_mx_staged<2, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
         return launch_mx_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream,
                                             workspace ? mx_split_k(M, N, Kp) : 1, workspace);
     }
     if (nb >= 8 && offsets_fit) {
         // any K' that is a multiple of 32, operands at their minimum alignment: units through registers
-        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-        if (t256 >= 256)
+        if (tile_rows == 256)
             return launch_mx_staged<4, 4, 2, 2, OutT, false, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
-        const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
-        if (t128x256 >= 192)
+        if (tile_rows == 192)
+            return launch_mx_staged<3, 4, 2, 2, OutT, false, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
+        if (tile_rows == 128)
             return launch_mx_staged<2, 4, 2, 2, OutT, false, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
         return launch_mx_staged<2, 2, 2, 2, OutT, false, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream,
                                                                workspace ? mx_split_k(M, N, Kp) : 1, workspace);

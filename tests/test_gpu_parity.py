@@ -648,6 +648,8 @@ MX_GEMM_SHAPES = [  # M, N, K, S: fallback kernel (K' % 128 != 0), every staged 
     (17, 14336, 512, 480),
     # three and four weight tiles per wave on the weight-streaming kernel
     (16, 10240, 512, 0), (32, 9000, 256, 64), (32, 12400, 512, 32),
+    # 192 x 256 tiles: whole units, a half unit at the end, units through registers
+    (570, 14000, 512, 0), (1100, 8000, 256, 128), (570, 14000, 256, 96),
     # the same on the tiled kernels, units through registers: 128 x 128 tiles without and with split K' (the last unit
     # holds 1, 7 and 5 blocks), 128 x 256 and 256 x 256 tiles
     (257, 131, 1024, 32), (300, 77, 2048, 2016), (500, 260, 4096, 160), (1990, 4070, 256, 96), (4000, 4100, 288, 32),
