@@ -316,9 +316,6 @@ int gemm_ksplit_variant(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nbk = Kp >> 4;
     if ((nbk & 15) != 0 || nbk < 32) return 0;            // whole stages of 256 k, at least two
     if ((uint64_t)M * (uint64_t)nbk * 8 >= 0xFFFF0000ull || (uint64_t)N * (uint64_t)nbk * 8 >= 0xFFFF0000ull) return 0;
-#ifdef ARCQ_KSPLIT_FORCE
-    return ARCQ_KSPLIT_FORCE;
-#endif
     // The smallest tile that still covers the problem with at most one workgroup per compute unit (256), as long as
     // it occupies more than half of them (measured at 4096 x 4352, 14336 x 4352 and 4096 x 14592 weights, M = 128 ..
     // 1024: against the 128 x 128 tiles with K' split across workgroups these run 64 x 64 tiles 1.2-1.8x, 128 x 64
