@@ -35,7 +35,7 @@ bf16 kernel arcq_ref_gemm_bf16): the 16-bit baselines of `linear_vs_*` (> 1: the
 faster).  The decode shapes c3a/c3b are weight-streaming bound: their `gemm_rotating_ms` cycles over
 enough weight copies to exceed the last-level cache, so every launch streams its weight from HBM.
 `s_sweep` times quantizer and GEMM against S at the LLaMA-3-8B q_proj shape (Section 3.4: cost linear
-in S/K); `machine` holds what the box itself reaches: the plain copy rate and the register-only matrix
+in S/K; S = 272 is there to show the step an S off the grid of 64 costs); `machine` holds what the box itself reaches: the plain copy rate and the register-only matrix
 instruction rates (arcq_probe_mfma_f16, arcq_probe_mfma_fp4).
 """
 import argparse
@@ -350,6 +350,7 @@ def s_sweep(torch, B, case, values):
     for r in rows:
         r["gemm_vs_S0"] = round(r["gemm_ms"] / g0, 4) if g0 else None
         r["Kp_vs_K"] = round((wl.K + r["S"]) / wl.K, 4)
+        r["Kp_mod_64"] = (wl.K + r["S"]) % 64       # non-zero: stages staged through registers instead of copied into LDS
     return rows
 
 
@@ -434,7 +435,7 @@ def main():
                     help="comma-separated extra workloads reported under 'also' (loop lengths from their own step time); '' for none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-vendor-ref", action="store_true")
-    ap.add_argument("--s-sweep", default="0,128,256,512,1024,2048",
+    ap.add_argument("--s-sweep", default="0,128,256,272,512,1024,2048",
                     help="values of S timed at the LLaMA-3-8B q_proj shape, reported under 's_sweep'; '' for none")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run three plain 1 GiB device copies (a kernel of known traffic, for scaling "
