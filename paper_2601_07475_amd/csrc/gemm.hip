@@ -1067,14 +1067,16 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
         // tiles per wave: as few as give the chip at most one workgroup per compute unit (256), up to four (three with
         // 17 to 32 activation rows); measured with weights from HBM at 16 rows: 640 tiles (N = 10240, K' = 8448) 13.7 us
         // with three tiles per wave against 18.1 us with two (320 workgroups: two rounds), 576 tiles 8.7 against 10.6
-        const int64_t T3 = 513, T4 = 769;
+        // (257 to 399 tiles used to run one tile per wave, two workgroups sharing a CU: 320 tiles over K' = 27904 33.7 us
+        // against 27.3 us with two tiles per wave, over K' = 4352 7.6 against 6.9)
+        const int64_t T2 = 257, T3 = 513, T4 = 769;
 #define ARCQ_SKINNY_W(MT_, NT_, W_, U_) \
     return launch_skinny<MT_, NT_, W_, U_, (MT_ <= 4)>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream)
 #define ARCQ_SKINNY(MT_, NT_, U_) ARCQ_SKINNY_W(MT_, NT_, 8, U_)
         if (M <= 16) {
             if (tiles >= T4) ARCQ_SKINNY(1, 4, 1);
             if (tiles >= T3) ARCQ_SKINNY(1, 3, 1);
-            if (tiles >= 400) ARCQ_SKINNY(1, 2, 2);
+            if (tiles >= T2) ARCQ_SKINNY(1, 2, 2);
             ARCQ_SKINNY(1, 1, 2);
         }
         if (M <= 32) {
@@ -1082,11 +1084,12 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
             // 14.7 with two against 17.9, 896 tiles 12.4 with four against 15.7 with two)
             if (tiles >= T4) ARCQ_SKINNY(2, 4, 1);
             if (tiles >= T3) ARCQ_SKINNY(2, 3, 1);
-            if (tiles >= 400) ARCQ_SKINNY(2, 2, 1);
+            if (tiles >= T2) ARCQ_SKINNY(2, 2, 1);
             ARCQ_SKINNY(2, 1, 2);
         }
         if (M <= 64) {
-            if (tiles >= 800) ARCQ_SKINNY(4, 2, 1);
+            // (64 rows, weights from HBM: 512 tiles over K' = 8464 23.2 us with two tiles per wave against 34.6 with one)
+            if (tiles >= T2) ARCQ_SKINNY(4, 2, 1);
             ARCQ_SKINNY(4, 1, 1);
         }
         if (tiles >= 800) ARCQ_SKINNY_W(8, 2, 4, 1);

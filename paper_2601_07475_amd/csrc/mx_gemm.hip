@@ -605,27 +605,28 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
     const bool offsets_fit = (uint64_t)M * (uint64_t)nb * 16 < 0xFFFF0000ull && (uint64_t)N * (uint64_t)nb * 16 < 0xFFFF0000ull;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
                            ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 3) == 0;
-    const bool streaming = mx_streaming_shape(M, N, Kp);
+    // up to 64 rows the tiled kernels only win where they can split K' across workgroups, which needs the workspace
+    const bool streaming = mx_streaming_shape(M, N, Kp) || (M <= 64 && workspace == nullptr && mx_split_k(M, N, Kp) > 1);
     if (streaming) {
         const int64_t tiles = (N + 15) / 16;
 #define ARCQ_MX_SKINNY(MT_, NT_, W_, U_) \
     return launch_mx_skinny<MT_, NT_, W_, U_>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream)
         // weight tiles per wave: as few as keep the launch at one workgroup per compute unit, up to four (measured with
         // weights from HBM, 32 rows: 640 tiles 14.8 us with three per wave against 21.7 with one, 896 tiles 10.4 us
-        // with four against 13.0 with two)
+        // with four against 13.0 with two, 320 tiles over K' = 8448 11.2 us with two against 15.2 with one)
         if (M <= 16) {
             if (tiles >= 769) ARCQ_MX_SKINNY(1, 4, 8, 1);
             if (tiles >= 513) ARCQ_MX_SKINNY(1, 3, 8, 1);
-            if (tiles >= 400) ARCQ_MX_SKINNY(1, 2, 8, 2);
+            if (tiles >= 257) ARCQ_MX_SKINNY(1, 2, 8, 2);
             ARCQ_MX_SKINNY(1, 1, 8, 2);
         }
         if (M <= 32) {
             if (tiles >= 769) ARCQ_MX_SKINNY(2, 4, 8, 1);
             if (tiles >= 513) ARCQ_MX_SKINNY(2, 3, 8, 1);
-            if (tiles >= 400) ARCQ_MX_SKINNY(2, 2, 8, 1);
+            if (tiles >= 257) ARCQ_MX_SKINNY(2, 2, 8, 1);
             ARCQ_MX_SKINNY(2, 1, 8, 2);
         }
-        if (tiles >= 800) ARCQ_MX_SKINNY(4, 2, 8, 1);
+        if (tiles >= 257) ARCQ_MX_SKINNY(4, 2, 8, 1);
         ARCQ_MX_SKINNY(4, 1, 8, 1);
 #undef ARCQ_MX_SKINNY
     }
