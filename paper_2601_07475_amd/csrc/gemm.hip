@@ -1137,6 +1137,15 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
             }
             return launch_staged<2, 2, 2, 4>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
         }
+        // More than 256 tiles of 128 x 128 (two workgroups on some compute units, one on the others) but at most 256 of
+        // 192 x 128: one round of the taller tile, which also decodes five fragments per six matrix instructions
+        // instead of four per four (1.52 against 1.3 us per stage and tile): 512 x 10240 over K' = 8448 116 -> 100 us,
+        // 1024 x 5120 over 27904 365 -> 297 us, 1280 x 4096 over 4352 61 -> 49 us.
+        {
+            const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128), t192 = ((M + 191) / 192) * ((N + 127) / 128);
+            if (t128 > 256 && t192 <= 256)
+                return launch_staged<3, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+        }
         return launch_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream,
                                          split_k(M, N, Kp), workspace);
     }

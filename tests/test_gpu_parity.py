@@ -296,6 +296,8 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     (50, 9300, 512, 0), (64, 14336, 256, 256), (33, 9216, 1024, 0),
     # 64 x 32 tiles (two fragments over four k-quarter waves: two of the waves finish none)
     (64, 6100, 512, 0), (100, 4000, 768, 256), (40, 5000, 4096, 256), (128, 500, 512, 0), (200, 1000, 4096, 256),
+    # 192 x 128 tiles (more than 256 tiles of 128 x 128, too few for the 256-wide ones): ragged edges, a half stage at the end
+    (500, 10200, 192, 64), (640, 8100, 256, 64),
     # 192 x 256 tiles (one round of them where 128-row tiles need two): ragged edges, whole stages and a half stage at the end;
     # 256 x 256 tiles that fill only part of the chip (fewer than 256 of them)
     (570, 14000, 192, 64), (1100, 8000, 256, 64), (1000, 14100, 128, 64),
