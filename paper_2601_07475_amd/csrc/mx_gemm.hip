@@ -581,6 +581,7 @@ int mx_split_k(int64_t M, int64_t N, int64_t Kp) {
     if (streaming || nb < 8) return 1;
     if (((M + 255) / 256) * ((N + 255) / 256) >= 256 || ((M + 127) / 128) * ((N + 255) / 256) >= 192) return 1;
     const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    if (tiles > 256 && ((M + 191) / 192) * ((N + 127) / 128) <= 256) return 1;      // one round of 192 x 128 tiles
     const int64_t nunit = (nb + 7) >> 3;
     const int64_t max_splits = std::min<int64_t>(8, nunit / 2);
     int best = 1;
@@ -646,6 +647,13 @@ arcq_status launch_mx_typed(const uint8_t* a_codes, const uint8_t* a_scales, con
             return launch_mx_staged<3, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
         if (tile_rows == 128)
             return launch_mx_staged<2, 4, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
+        // more than 256 tiles of 128 x 128 but at most 256 of 192 x 128: one round of the taller tile instead of two
+        // workgroups on some compute units (512 x 10240 over K' = 8448: 48 -> 37 us; 1024 x 5120 over 27904: 144 -> 105 us)
+        {
+            const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128), t192 = ((M + 191) / 192) * ((N + 127) / 128);
+            if (t128 > 256 && t192 <= 256)
+                return launch_mx_staged<3, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream);
+        }
         return launch_mx_staged<2, 2, 2, 2>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nb, y, ldy, stream,
                                             workspace ? mx_split_k(M, N, Kp) : 1, workspace);
     }

@@ -650,6 +650,8 @@ MX_GEMM_SHAPES = [  # M, N, K, S: fallback kernel (K' % 128 != 0), every staged 
     (17, 14336, 512, 480),
     # three and four weight tiles per wave on the weight-streaming kernel
     (16, 10240, 512, 0), (32, 9000, 256, 64), (32, 12400, 512, 32),
+    # 192 x 128 tiles (more than 256 tiles of 128 x 128, too few for the 256-wide ones): a whole unit, a half unit at the end
+    (500, 10200, 256, 0), (640, 8100, 256, 128),
     # 192 x 256 tiles: whole units, a half unit at the end, units through registers
     (570, 14000, 512, 0), (1100, 8000, 256, 128), (570, 14000, 256, 96),
     # the same on the tiled kernels, units through registers: 128 x 128 tiles without and with split K' (the last unit
