@@ -104,7 +104,11 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
     const int wg_m0 = tile_m * C::BM, wg_n0 = tile_n * C::BN;
     const int wrow0 = (wq / GN) * (32 * WM);         // first row of this wave inside the A tile
     const int wcol0 = (wq % GN) * (32 * WN);         // first row of this wave inside the W tile
-    const int nstage = nbk / (4 * KS);               // stages of 4 KS blocks (the launcher checks divisibility)
+    // stages of 4 KS blocks; the last one may hold only `part` k shares (K' is a multiple of 64, not of 64 KS): the
+    // copies of its missing shares re-fetch the first share (in bounds, never used) and the waves of those shares read
+    // their scale bytes as zero, so that their fragments decode to zeros
+    const int nstage = (nbk + 4 * KS - 1) / (4 * KS);
+    const int part = (nbk % (4 * KS)) / 4;           // 0: the last stage is whole
 
     // ---- copies
     auto swz = [](int row) -> uint32_t { return KS == 4 ? (uint32_t)(row >> 1) & 7u : (uint32_t)(row >> 2) & 3u; };
@@ -114,10 +118,14 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
     const uint32_t cpitch32 = (uint32_t)nbk * 8u, spitch32 = (uint32_t)nbk;
     const uint32_t wave_slot = __builtin_amdgcn_readfirstlane((uint32_t)(tid & ~63));
     const uint32_t lds0 = lds_address(lds);
+    const uint32_t piece_g = (uint32_t)(tid % C::PPR) ^ swz(crow);      // global piece this lane fetches
+    const bool piece_missing = part != 0 && (int)(piece_g >> 1) >= part, scale_missing = part != 0 && tid % KS >= part;
+    const uint32_t adj_c_last = piece_missing ? 16u * (piece_g & 1u) : adj_c, adj_s_last = scale_missing ? 0u : adj_s;
     auto issue_one = [&](int d, int stage, int buf) {
         const uint32_t base = lds0 + buf * C::STAGE_BYTES;
-        const uint32_t oc = (uint32_t)stage * C::ROWB + adj_c;
-        const uint32_t os = (uint32_t)stage * C::SROWB + adj_s;
+        const bool last = stage == nstage - 1;
+        const uint32_t oc = (uint32_t)stage * C::ROWB + (last ? adj_c_last : adj_c);
+        const uint32_t os = (uint32_t)stage * C::SROWB + (last ? adj_s_last : adj_s);
         constexpr int NA = C::NA, NW = C::NW, NAS = C::NAS, NT = C::NT;
         // rows past the edge of the operand re-read its last row (never stored)
         if (d < NA) {
@@ -160,16 +168,19 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
     uint4 ca[WM], cw[WN];
     uint32_t sa[WM], sw[WN];
     half8 fa[2][WM], fw[2][WN];
-    auto read_raw = [&](const uint8_t* st) {
+    const bool share_missing = part != 0 && kh >= part;     // this wave has nothing in the last stage
+    auto read_raw = [&](const uint8_t* st, bool zero) {
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
             ca[i] = *reinterpret_cast<const uint4*>(st + rd_a + i * (32 * C::ROWB));
-            sa[i] = scale_halves(*reinterpret_cast<const uint32_t*>(st + rd_as + i * (32 * C::SROWB)), scale_sel);
+            const uint32_t word = *reinterpret_cast<const uint32_t*>(st + rd_as + i * (32 * C::SROWB));
+            sa[i] = scale_halves(zero ? 0u : word, scale_sel);
         }
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             cw[j] = *reinterpret_cast<const uint4*>(st + rd_w + j * (32 * C::ROWB));
-            sw[j] = scale_halves(*reinterpret_cast<const uint32_t*>(st + rd_ws + j * (32 * C::SROWB)), scale_sel);
+            const uint32_t word = *reinterpret_cast<const uint32_t*>(st + rd_ws + j * (32 * C::SROWB));
+            sw[j] = scale_halves(zero ? 0u : word, scale_sel);
         }
     };
     auto decode_frag = [&](int gidx, int t) {   // fragment gidx of this wave's k-step t (0..3) into slot t & 1
@@ -201,7 +212,7 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
             if (t == 3) {
                 wait_vmcnt<(C::DIST - 1) * C::NDMA>();
                 wg_barrier();
-                read_raw(lds + buf1 * C::STAGE_BYTES);
+                read_raw(lds + buf1 * C::STAGE_BYTES, share_missing && s + 1 >= nstage - 1);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -234,7 +245,7 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
         for (int q = 0; q < C::NDMA; ++q) issue_one(q, min(d, nstage - 1), d);
     wait_vmcnt<(C::DIST - 1) * C::NDMA>();
     wg_barrier();
-    read_raw(lds);
+    read_raw(lds, share_missing && nstage == 1);
 #pragma unroll
     for (int gidx = 0; gidx < G; ++gidx) decode_frag(gidx, 0);
     for (int s = 0; s < nstage; ++s) run_stage(s);
@@ -314,7 +325,7 @@ arcq_status launch_ksplit_typed(int variant, const uint8_t* a_codes, const uint8
 // 0: not served here; 6: 64 x 32 tiles; 1: 64 x 64; 4: 96 x 64; 2: 128 x 64; 3: 128 x 128 (k quarters inside the workgroup each)
 int gemm_ksplit_variant(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nbk = Kp >> 4;
-    if ((nbk & 15) != 0 || nbk < 32) return 0;            // whole stages of 256 k, at least two
+    if ((nbk & 3) != 0 || nbk < 32) return 0;             // K' a multiple of 64 (whole k shares), at least two stages
     if ((uint64_t)M * (uint64_t)nbk * 8 >= 0xFFFF0000ull || (uint64_t)N * (uint64_t)nbk * 8 >= 0xFFFF0000ull) return 0;
     // The smallest tile that still covers the problem with at most one workgroup per compute unit (256), as long as
     // it occupies more than half of them (measured at 4096 x 4352, 14336 x 4352 and 4096 x 14592 weights, M = 128 ..

@@ -287,6 +287,9 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     # between 144 and 256 tiles of 64 x 64, 128 x 64 or 128 x 128 and K' a multiple of 256: the kernel whose waves split
     # every stage into k quarters inside the workgroup (ragged edges in both directions; two, five and 17 stages)
     (130, 3100, 512, 0), (192, 4096, 4096, 256), (300, 3500, 1024, 256), (700, 3900, 448, 64), (1024, 4096, 1024, 256),
+    # ... K' a multiple of 64 but not of 256: the last stage holds one, two or three of the four k shares (every tile shape)
+    (130, 3100, 512, 64), (192, 4096, 1024, 128), (300, 3500, 1024, 192), (1024, 4096, 512, 64), (512, 4000, 512, 192),
+    (64, 6100, 512, 64), (700, 3900, 448, 128),
     # ... 96 x 64 tiles (six fragments over four waves: two waves finish two, two finish one), exact and ragged; 128 x 64
     (384, 4096, 1024, 0), (290, 3500, 512, 256), (512, 4000, 512, 0),
     # three weight tiles per wave on the weight-streaming kernel (513 to 768 tiles of 16 weight rows), 16 and 32 rows
