@@ -790,7 +790,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     int nbk, float alpha, OutT* __restrict__ y, int64_t ldy) {
     __shared__ float red[WAVES][MT * NT][4][64];
     static_assert(sizeof(float) * WAVES * MT * NT * 256 <= 64 * 1024, "partial tiles must fit the static LDS limit");
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the wave number as a scalar: conditions on it become scalar branches (a matrix instruction inside a branch on a
+    // vector condition would still execute: it does not honour the lane mask)
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int i = lane & 15, q = lane >> 4;
     const int n0 = blockIdx.x * (16 * NT);
     const int64_t cpitch = (int64_t)nbk * 8, spitch = nbk;
@@ -924,11 +926,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(
     bool grouped = false;
     if constexpr (GRP) grouped = nbk >= 32;
     if (grouped) {
-        // Whole chunks in groups of four, dealt round-robin to the waves; the up to three chunks behind the last
+        // Whole chunks in groups of four, dealt round-robin to the waves; the up to four chunks behind the last
         // group go to the waves that took one group less.  With one group per wave and four tiles (the up-projection
         // shapes) such a wave asks for its left-over chunk FIRST and decodes it last, so that it costs no trip to
         // memory of its own (1 us of 12 there); with few tiles per wave and several groups the same change made the
-        // kernel 10 % slower (measured), so those variants load it where they use it.
+        // kernel 10 % slower (measured), so those variants load it where they use it.  (Dealing the left-over chunks
+        // out as (chunk, tile) units, one per wave, balances the waves but decodes the activation chunk once per unit:
+        // 11.7 against 10.5 us on the 16 x 14336 x 4352 shape, not kept.)
         constexpr bool HOIST = MT == 1 && NT == 4;
         const int ngroup = nbk >> 5;
         const int tail_c = 4 * ngroup + (wave - ngroup % WAVES + WAVES) % WAVES * U;

@@ -324,7 +324,7 @@ __global__ __launch_bounds__(256) void mx_gemm_direct_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N, int nb,
     OutT* __restrict__ y, int64_t ldy) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // scalar: see gemm.hip
     const int r = lane & 31, h = lane >> 5;
     const int m0 = blockIdx.y * 128 + (wave >> 1) * 64, n0 = blockIdx.x * 128 + (wave & 1) * 64;
     const int64_t cpitch = (int64_t)nb * 16, spitch = nb;
@@ -400,7 +400,7 @@ __global__ __launch_bounds__(WAVES * 64) void mx_gemm_skinny_kernel(
     OutT* __restrict__ y, int64_t ldy) {
     __shared__ float red[WAVES][MT * NT][4][64];
     static_assert(sizeof(float) * WAVES * MT * NT * 256 <= 64 * 1024, "partial tiles must fit the static LDS limit");
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // scalar: see gemm.hip
     const int i = lane & 15, q = lane >> 4;
     const int n0 = blockIdx.x * (16 * NT);
     const int64_t cpitch = (int64_t)nb * 16, spitch = nb;

@@ -292,6 +292,9 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     (64, 6100, 512, 64), (700, 3900, 448, 128),
     # ... 96 x 64 tiles (six fragments over four waves: two waves finish two, two finish one), exact and ragged; 128 x 64
     (384, 4096, 1024, 0), (290, 3500, 512, 256), (512, 4000, 512, 0),
+    # four weight tiles per wave at up to 16 rows, left-over chunks behind the last group of four: 2 chunks (the last one
+    # block), 1 chunk of two blocks, 4 chunks (the last six blocks), none
+    (5, 12400, 656, 0), (16, 13000, 1040, 16), (9, 12320, 992, 0), (16, 12304, 1024, 0),
     # three weight tiles per wave on the weight-streaming kernel (513 to 768 tiles of 16 weight rows), 16 and 32 rows
     (16, 10240, 512, 32), (9, 8300, 1040, 16), (32, 9000, 256, 64), (20, 12288, 4096, 256), (32, 7000, 512, 0),
     (32, 12400, 528, 0),
