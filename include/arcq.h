@@ -188,7 +188,7 @@ arcq_status arcq_gemm(const uint8_t* a_codes, const uint8_t* a_scales, float a_t
  *     concurrently) race on it; order them.  Nothing in it has to start at zero (every partial result is written
  *     before it is read), and its contents are undefined afterwards.
  */
-#define ARCQ_NOALLOC_SCRATCH_BYTES (32u << 20)
+#define ARCQ_NOALLOC_SCRATCH_BYTES (8u << 20)
 arcq_status arcq_gemm_noalloc(const uint8_t* a_codes, const uint8_t* a_scales, float a_tensor_scale,
                               const uint8_t* w_codes, const uint8_t* w_scales, float w_tensor_scale,
                               int64_t M, int64_t N, int64_t Kp,

@@ -189,7 +189,7 @@ def arcq_gemm(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_sca
     return y
 
 
-NOALLOC_SCRATCH_BYTES = 32 << 20
+NOALLOC_SCRATCH_BYTES = 8 << 20
 
 
 def arcq_gemm_noalloc(a_codes, a_scales, a_tensor_scale, w_codes, w_scales, w_tensor_scale, y):

@@ -1060,7 +1060,7 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
     // fragment once per tile, the weight-streaming kernel once per 32 weight rows
     // (measured with weights from HBM, 64 rows: 14336 x 4352 15.8 us against 21.8, 9216 x 4352 15.3 against 25.3,
     // 12288 x 8448 25.0 against 44.8; 33 rows gain as long as the tiles are 64 x 64)
-    const int ks_variant = M > 32 && aligned16 ? gemm_ksplit_variant(M, N, Kp) : 0;
+    const int ks_variant = M > 32 ? gemm_ksplit_variant(M, N, Kp) : 0;
     const bool tiles_instead = ks_variant == 1 || ks_variant == 6 || (ks_variant != 0 && M > 48);
     if (skinny_shape(M, N, Kp) && !tiles_instead) {
         // Weight-streaming path.  Enough waves to keep the weight stream in flight, as few as that allows
@@ -1102,10 +1102,9 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
 #undef ARCQ_SKINNY_W
     }
     const bool offsets_fit = (uint64_t)M * (uint64_t)nbk * 8 < 0xFFFF0000ull && (uint64_t)N * (uint64_t)nbk * 8 < 0xFFFF0000ull;
-    if (aligned16)
-        if (const int variant = gemm_ksplit_variant(M, N, Kp))
-            return launch_gemm_ksplit(variant, a_codes, a_scales, w_codes, w_scales, M, N, Kp, alpha, y,
-                                      std::is_same<OutT, _Float16>::value ? ARCQ_DTYPE_F16 : ARCQ_DTYPE_F32, ldy, stream);
+    if (const int variant = gemm_ksplit_variant(M, N, Kp))
+        return launch_gemm_ksplit(variant, a_codes, a_scales, w_codes, w_scales, M, N, Kp, alpha, y,
+                                  std::is_same<OutT, _Float16>::value ? ARCQ_DTYPE_F16 : ARCQ_DTYPE_F32, ldy, stream);
     if ((nbk & 3) == 0 && nbk >= 8 && offsets_fit && aligned16) {
         // Tiles of 256 weight rows by 256, 192 or 128 activation rows when there is work for them.  Workgroups run in
         // rounds of one per compute unit and a round lasts as long as one tile, so the tile height that minimises

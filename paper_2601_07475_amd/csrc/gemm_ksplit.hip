@@ -73,7 +73,12 @@ __device__ __forceinline__ void store_fragment(const float16v& a, int m0, int n0
     }
 }
 
-template <int WM, int WN, int GM, int GN, int KS, typename OutT>
+// REG: any K' (a multiple of 16) and operands that are only 8-byte aligned: a thread fetches its pieces of stage s + 2
+// into registers with ordinary loads (declared with the alignment the interface guarantees), right after the barrier
+// that opens stage s + 1, and writes them to LDS before the barrier that opens their stage; blocks past the end of a row
+// become zero codes and zero scale bytes (a piece that would reach past the row's end is fetched from further left and
+// shifted), so the last stage needs no special case.
+template <int WM, int WN, int GM, int GN, int KS, typename OutT, bool REG = false>
 __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
     const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
     const uint8_t* __restrict__ w_codes, const uint8_t* __restrict__ w_scales, int M, int N,
@@ -108,7 +113,7 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
     // copies of its missing shares re-fetch the first share (in bounds, never used) and the waves of those shares read
     // their scale bytes as zero, so that their fragments decode to zeros
     const int nstage = (nbk + 4 * KS - 1) / (4 * KS);
-    const int part = (nbk % (4 * KS)) / 4;           // 0: the last stage is whole
+    const int part = REG ? 0 : (nbk % (4 * KS)) / 4; // 0: the last stage is whole (REG: made whole with zeros)
 
     // ---- copies
     auto swz = [](int row) -> uint32_t { return KS == 4 ? (uint32_t)(row >> 1) & 7u : (uint32_t)(row >> 2) & 3u; };
@@ -143,6 +148,48 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
             const int p = d - NA - NW - NAS;
             const uint32_t row = (uint32_t)min(wg_n0 + p * (NT / KS) + srow, N - 1);
             dma4(w_scales, row * spitch32 + os, base + C::W_SCALES + 4u * (p * NT + wave_slot));
+        }
+    };
+
+    // ---- REG: the same pieces through registers (piece d of a thread lands where copy d puts it); needs nbk >= 4
+    constexpr int NCP = C::NA + C::NW, NSP = C::NAS + C::NWS;
+    uint4 rc[REG ? NCP : 1];
+    uint32_t rs[REG ? NSP : 1];
+    auto reg_issue = [&](int stage) {
+        const uint32_t oc = 8u * (uint32_t)min(4 * KS * stage + 2 * (int)piece_g, nbk - 2);
+#pragma unroll
+        for (int d = 0; d < NCP; ++d) {
+            const bool is_a = d < C::NA;
+            const int p = is_a ? d : d - C::NA;
+            const uint32_t row = (uint32_t)(is_a ? min(wg_m0 + p * (C::NT / C::PPR) + crow, M - 1) : min(wg_n0 + p * (C::NT / C::PPR) + crow, N - 1));
+            rc[d] = load16_a8((is_a ? a_codes : w_codes) + (size_t)(row * cpitch32 + oc));
+        }
+        const uint32_t os = (uint32_t)min(4 * KS * stage + 4 * (tid % KS), nbk - 4);
+#pragma unroll
+        for (int d = 0; d < NSP; ++d) {
+            const bool is_a = d < C::NAS;
+            const int p = is_a ? d : d - C::NAS;
+            const uint32_t row = (uint32_t)(is_a ? min(wg_m0 + p * (C::NT / KS) + srow, M - 1) : min(wg_n0 + p * (C::NT / KS) + srow, N - 1));
+            rs[d] = load4_a1((is_a ? a_scales : w_scales) + (size_t)(row * spitch32 + os));
+        }
+    };
+    auto reg_commit = [&](int stage, int buf) {
+        uint8_t* st = lds + buf * C::STAGE_BYTES;
+        const int b0 = 4 * KS * stage + 2 * (int)piece_g;      // this piece: blocks b0, b0 + 1
+        const bool both = b0 + 1 < nbk, one = b0 < nbk;
+#pragma unroll
+        for (int d = 0; d < NCP; ++d) {
+            const uint4 v = uint4{both ? rc[d].x : one ? rc[d].z : 0u, both ? rc[d].y : one ? rc[d].w : 0u, both ? rc[d].z : 0u, both ? rc[d].w : 0u};
+            const int at = d < C::NA ? C::A_CODES + 16 * (d * C::NT + tid) : C::W_CODES + 16 * ((d - C::NA) * C::NT + tid);
+            *reinterpret_cast<uint4*>(st + at) = v;
+        }
+        const int sb0 = 4 * KS * stage + 4 * (tid % KS);       // this word: blocks sb0 .. sb0 + 3
+        const int skip = sb0 - min(sb0, nbk - 4);               // bytes of the fetched word that belong to earlier blocks
+#pragma unroll
+        for (int d = 0; d < NSP; ++d) {
+            const uint32_t word = skip >= 4 ? 0u : rs[d] >> (8 * skip);
+            const int at = d < C::NAS ? C::A_SCALES + 4 * (d * C::NT + tid) : C::W_SCALES + 4 * ((d - C::NAS) * C::NT + tid);
+            *reinterpret_cast<uint32_t*>(st + at) = word;
         }
     };
 
@@ -210,9 +257,15 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             if (t == 3) {
-                wait_vmcnt<(C::DIST - 1) * C::NDMA>();
+                if constexpr (REG) {
+                    reg_commit(min(s + 1, nstage - 1), buf1);       // fetched since step 3 of the stage before
+                    wait_lgkmcnt0();
+                } else {
+                    wait_vmcnt<(C::DIST - 1) * C::NDMA>();
+                }
                 wg_barrier();
                 read_raw(lds + buf1 * C::STAGE_BYTES, share_missing && s + 1 >= nstage - 1);
+                if constexpr (REG) reg_issue(min(s + 2, nstage - 1));
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -227,7 +280,7 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[t & 1][j], fa[t & 1][i], acc[i][j], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (t < 3) {
+                if (!REG && t < 3) {
 #pragma unroll
                     for (int d = 0; d < C::NDMA; ++d)
                         if ((d * 3) / C::NDMA == t && (d - (t * C::NDMA + 2) / 3) == p) issue_one(d, fetch, buf2);
@@ -239,11 +292,18 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
     };
     static_assert((C::NDMA + 2) / 3 <= P, "the copies of a stage are spread over the MFMAs of three k-steps");
 
+    if constexpr (REG) {
+        reg_issue(0);
+        reg_commit(0, 0);
+        reg_issue(min(1, nstage - 1));
+        wait_lgkmcnt0();
+    } else {
 #pragma unroll
-    for (int d = 0; d < C::DIST; ++d)
+        for (int d = 0; d < C::DIST; ++d)
 #pragma unroll
-        for (int q = 0; q < C::NDMA; ++q) issue_one(q, min(d, nstage - 1), d);
-    wait_vmcnt<(C::DIST - 1) * C::NDMA>();
+            for (int q = 0; q < C::NDMA; ++q) issue_one(q, min(d, nstage - 1), d);
+        wait_vmcnt<(C::DIST - 1) * C::NDMA>();
+    }
     wg_barrier();
     read_raw(lds, share_missing && nstage == 1);
 #pragma unroll
@@ -294,11 +354,11 @@ __global__ __launch_bounds__(64 * GM * GN * KS) void gemm_ksplit_kernel(
         if (f % KS == kh) store_fragment(acc[f / WN][f % WN], m0 + 32 * (f / WN), n0 + 32 * (f % WN), r, h, M, N, alpha, y, ldy, vec_ok);
 }
 
-template <int WM, int WN, int GM, int GN, int KS, typename OutT>
+template <int WM, int WN, int GM, int GN, int KS, bool REG, typename OutT>
 arcq_status launch_ksplit(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes, const uint8_t* w_scales,
                           int M, int N, int nbk, float alpha, OutT* y, int64_t ldy, hipStream_t stream) {
     using C = KsplitCfg<WM, WN, GM, GN, KS>;
-    auto kern = gemm_ksplit_kernel<WM, WN, GM, GN, KS, OutT>;
+    auto kern = gemm_ksplit_kernel<WM, WN, GM, GN, KS, OutT, REG>;
     static std::atomic<uint64_t> lds_raised{0};
     if (arcq_status st = raise_lds_limit(reinterpret_cast<const void*>(kern), lds_raised)) return st;
     const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
@@ -307,16 +367,16 @@ arcq_status launch_ksplit(const uint8_t* a_codes, const uint8_t* a_scales, const
     return check_launch("gemm_ksplit_kernel");
 }
 
-template <typename OutT>
+template <bool REG, typename OutT>
 arcq_status launch_ksplit_typed(int variant, const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* w_codes,
                                 const uint8_t* w_scales, int M, int N, int nbk, float alpha, OutT* y, int64_t ldy,
                                 hipStream_t stream) {
     switch (variant) {
-        case 1: return launch_ksplit<2, 2, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 64 x 64
-        case 2: return launch_ksplit<4, 2, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 128 x 64
-        case 4: return launch_ksplit<3, 2, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 96 x 64
-        case 6: return launch_ksplit<2, 1, 1, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 64 x 32
-        default: return launch_ksplit<2, 4, 2, 1, 4>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);  // 128 x 128
+        case 1: return launch_ksplit<2, 2, 1, 1, 4, REG>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 64 x 64
+        case 2: return launch_ksplit<4, 2, 1, 1, 4, REG>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 128 x 64
+        case 4: return launch_ksplit<3, 2, 1, 1, 4, REG>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 96 x 64
+        case 6: return launch_ksplit<2, 1, 1, 1, 4, REG>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);   // 64 x 32
+        default: return launch_ksplit<2, 4, 2, 1, 4, REG>(a_codes, a_scales, w_codes, w_scales, M, N, nbk, alpha, y, ldy, stream);  // 128 x 128
     }
 }
 
@@ -325,7 +385,7 @@ arcq_status launch_ksplit_typed(int variant, const uint8_t* a_codes, const uint8
 // 0: not served here; 6: 64 x 32 tiles; 1: 64 x 64; 4: 96 x 64; 2: 128 x 64; 3: 128 x 128 (k quarters inside the workgroup each)
 int gemm_ksplit_variant(int64_t M, int64_t N, int64_t Kp) {
     const int64_t nbk = Kp >> 4;
-    if ((nbk & 3) != 0 || nbk < 32) return 0;             // K' a multiple of 64 (whole k shares), at least two stages
+    if (nbk < 32) return 0;                               // at least two stages
     if ((uint64_t)M * (uint64_t)nbk * 8 >= 0xFFFF0000ull || (uint64_t)N * (uint64_t)nbk * 8 >= 0xFFFF0000ull) return 0;
     // The smallest tile that still covers the problem with at most one workgroup per compute unit (256), as long as
     // it occupies more than half of them (measured at 4096 x 4352, 14336 x 4352 and 4096 x 14592 weights, M = 128 ..
@@ -350,11 +410,19 @@ arcq_status launch_gemm_ksplit(int variant, const uint8_t* a_codes, const uint8_
                                const uint8_t* w_scales, int64_t M, int64_t N, int64_t Kp, float alpha, void* y, int y_dtype,
                                int64_t ldy, hipStream_t stream) {
     const int nbk = (int)(Kp >> 4);
+    // direct-to-LDS copies need rows that start on 16-byte boundaries (K' a multiple of 64 covers the scale bytes too)
+    const bool copies = (nbk & 3) == 0 &&
+                        ((reinterpret_cast<uintptr_t>(a_codes) | reinterpret_cast<uintptr_t>(w_codes)) & 15) == 0 &&
+                        ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(w_scales)) & 3) == 0;
     if (y_dtype == ARCQ_DTYPE_F16)
-        return launch_ksplit_typed<_Float16>(variant, a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha,
-                                             static_cast<_Float16*>(y), ldy, stream);
-    return launch_ksplit_typed<float>(variant, a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha,
-                                      static_cast<float*>(y), ldy, stream);
+        return copies ? launch_ksplit_typed<false>(variant, a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha,
+                                                   static_cast<_Float16*>(y), ldy, stream)
+                      : launch_ksplit_typed<true>(variant, a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha,
+                                                  static_cast<_Float16*>(y), ldy, stream);
+    return copies ? launch_ksplit_typed<false>(variant, a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha,
+                                               static_cast<float*>(y), ldy, stream)
+                  : launch_ksplit_typed<true>(variant, a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha,
+                                              static_cast<float*>(y), ldy, stream);
 }
 
 }  // namespace arcq

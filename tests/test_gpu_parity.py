@@ -290,6 +290,9 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     # ... K' a multiple of 64 but not of 256: the last stage holds one, two or three of the four k shares (every tile shape)
     (130, 3100, 512, 64), (192, 4096, 1024, 128), (300, 3500, 1024, 192), (1024, 4096, 512, 64), (512, 4000, 512, 192),
     (64, 6100, 512, 64), (700, 3900, 448, 128),
+    # ... K' with an odd number of blocks, or K' % 64 = 32: the same tiles with stages through registers (every tile shape)
+    (130, 3100, 512, 16), (192, 4096, 1024, 48), (300, 3500, 1024, 208), (1024, 4096, 512, 16), (512, 4000, 512, 176),
+    (64, 6100, 512, 16),
     # ... 96 x 64 tiles (six fragments over four waves: two waves finish two, two finish one), exact and ragged; 128 x 64
     (384, 4096, 1024, 0), (290, 3500, 512, 256), (512, 4000, 512, 0),
     # four weight tiles per wave at up to 16 rows, left-over chunks behind the last group of four: 2 chunks (the last one

@@ -131,9 +131,10 @@ def test_gemm_noalloc_argument_errors_and_scratch_limit():
     assert ga(ac=ODD) == B.BAD_ALIGN and ga(y=ctypes.c_void_p(0x10002)) == B.BAD_ALIGN
     assert ga(M=0, ac=None, y=None) == B.OK
     n = ctypes.c_size_t(0)
-    assert B.lib().arcq_gemm_workspace_size(384, 4096, 65616, ctypes.byref(n)) == B.OK
-    assert n.value > B.NOALLOC_SCRATCH_BYTES == 32 << 20
-    assert ga(M=384, N=4096, Kp=65616, ldy=4096) == B.WORKSPACE_TOO_SMALL
+    # a few hundred rows against a few hundred weight rows over a very long reduction: K' split seven times
+    assert B.lib().arcq_gemm_workspace_size(896, 640, 14592, ctypes.byref(n)) == B.OK
+    assert n.value > B.NOALLOC_SCRATCH_BYTES == 8 << 20
+    assert ga(M=896, N=640, Kp=14592, ldy=640) == B.WORKSPACE_TOO_SMALL
     assert b"built-in" in B.lib().arcq_last_error()
 
 
