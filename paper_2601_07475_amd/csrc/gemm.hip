@@ -1153,9 +1153,19 @@ arcq_status launch_typed(const uint8_t* a_codes, const uint8_t* a_scales, const 
                                          split_k(M, N, Kp), workspace);
     }
     if (offsets_fit && nbk >= 8) {
-        // any K' that is a multiple of 16, operands that are only 8-byte aligned: stages through registers
-        if (((M + 127) / 128) * ((N + 255) / 256) >= 192)
+        // any K' that is a multiple of 16, operands that are only 8-byte aligned: stages through registers (no 256 x 256
+        // tiles: the staging registers do not fit beside 256 accumulators); the same choice by rounds x stage time
+        // (3.5 and 2.4 us measured per stage for 192 x 256 and 128 x 256 tiles: 768 x 14336 over K' = 4368 118 us instead of 163)
+        const int64_t tn256 = (N + 255) / 256;
+        if (((M + 127) / 128) * tn256 >= 192) {
+            auto cost = [&](int bm, double t_stage) { return (double)((((M + bm - 1) / bm) * tn256 + 255) / 256) * t_stage; };
+            if (cost(192, 3.5) <= cost(128, 2.4))
+                return launch_staged<3, 4, 2, 2, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
             return launch_staged<2, 2, 2, 4, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
+        }
+        const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128), t192 = ((M + 191) / 192) * ((N + 127) / 128);
+        if (t128 > 256 && t192 <= 256)
+            return launch_staged<3, 2, 2, 2, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream);
         return launch_staged<2, 2, 2, 2, true>(a_codes, a_scales, w_codes, w_scales, (int)M, (int)N, nbk, alpha, y, ldy, stream,
                                                split_k(M, N, Kp), workspace);
     }

@@ -318,6 +318,8 @@ GEMM_SHAPES = [  # M, N, K, S : ragged tiles, K' with every residue mod 64, tiny
     # holds 2, 7, 1 and 4 blocks), 128 x 256 tiles, and a large output
     (257, 131, 1040, 16), (200, 140, 560, 64), (300, 260, 4160, 80), (256, 512, 4096, 320), (1990, 4070, 240, 64),
     (2048, 3000, 1024, 144), (4000, 4100, 112, 64), (128, 1500, 8192, 528),
+    # ... 192 x 256 and 192 x 128 tiles with stages through registers
+    (570, 14000, 192, 80), (500, 10200, 192, 48),
 ]
 
 
